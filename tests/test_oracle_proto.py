@@ -1,0 +1,243 @@
+"""Pins for oracle/proto.py and oracle/brute.py (CPU only).
+
+What fixes the oracle from outside: the definition of the iteration gradient (brute-force
+exactly rounded sums over the committed ids), power-of-two coded gradients whose sum shows
+which microbatches are inside and how often, constant gradients (closed form), and the
+restoration invariants of Sec. 4.2 (a rewound bucket equals one that never took the lost
+work)."""
+import numpy as np
+import pytest
+
+from oracle import brute
+from oracle.policy import RESTORE_NONBLOCKING
+from oracle.proto import Proto, ProtocolError
+from paper_2605_11215_amd.synth import reference_np as S
+from tests.driver import run_iteration, view_oracle, HP
+
+OFF_RAGGED = [0, 1, 4, 9, 1032, 1037, 1100]          # tensor lengths 1, 3, 5, 1023, 5, 63
+
+
+def grads(seed, scale=1e-3, n=OFF_RAGGED[-1], bf16=False):
+    cache = {}
+
+    def grad_of(t, mb):
+        if (t, mb) not in cache:
+            g = S.fill(n, seed, S.TAG_GRAD, mb, t, scale)
+            cache[(t, mb)] = S.bf16_bits_to_f32(S.f32_to_bf16_bits(g)) if bf16 else g
+        return cache[(t, mb)]
+    return grad_of
+
+
+def new_proto(W, G, off=OFF_RAGGED, dtype=np.float64, seed=1, **kw):
+    p = Proto(W, G, off, dtype=dtype, **kw)
+    p.set_state(S.fill(off[-1], seed, S.TAG_PARAM, 0, 0, 0.02))
+    return p
+
+
+def test_tiny_schedule_quotas_and_ids():
+    """R=4, G=2, replica 2 dies after one microbatch of iteration 1: survivors end at
+    quotas 3, 3, 2 (sum 8) and the committed ids are the survivors' own slices."""
+    p = new_proto(4, 2)
+    g = grads(1)
+    out = run_iteration(p, view_oracle, 0, g, 4)
+    assert sorted(sum(out["ids"].values(), [])) == list(range(8))
+    out = run_iteration(p, view_oracle, 1, g, 4, dying={2: 1})
+    d = out["decisions"][0]
+    assert d["at_boundary"] and d["C_cur"] == 6 and d["G_ext"] == 1 and d["n_bdry"] == 1
+    assert out["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
+    adv = out["decisions"][-1]
+    assert (adv["G_cur"], adv["n_maj"], adv["R_cur"]) == (3, 2, 2)
+    out = run_iteration(p, view_oracle, 2, g, 4)
+    assert out["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
+
+
+@pytest.mark.parametrize("dtype,tol", [(np.float64, 1e-15), (np.float32, 2e-6)])
+def test_iteration_gradient_is_the_mean_over_committed_ids(dtype, tol):
+    """proto's grad_out against the exactly rounded sum over A(t), failure-free and not."""
+    p = new_proto(4, 2, dtype=dtype)
+    g = grads(3)
+    for t, dying in enumerate([None, {2: 1}, None, {0: 0, 3: 2}]):
+        captured = {}
+        out = run_iteration(p, view_oracle, t, g, 4, dying=dying,
+                            on_sync=lambda e: None)
+        ids = sum(out["ids"].values(), [])
+        assert len(ids) == 8 == len(set(ids))
+        want = brute.exact_mean([g(t, j) for j in ids], 8)
+        # grad_out of iteration t is still in the buffer after the step
+        got = p.grad_out.astype(np.float64)
+        assert np.max(np.abs(got - want)) <= tol * np.max(np.abs(want))
+        assert np.allclose(brute.mean64([g(t, j) for j in ids], 8), want, rtol=0, atol=1e-18)
+
+
+def coded(n=8):
+    """Microbatch j's gradient is 2**j in every element: a sum shows its terms as bits."""
+    def grad_of(t, mb):
+        return np.full(n, 2.0 ** mb, np.float64)
+    return grad_of
+
+
+def terms_of(x):
+    x = int(x)
+    return [j for j in range(x.bit_length()) if (x >> j) & 1]
+
+
+@pytest.mark.parametrize("fidelity_k", [0, 1, 2])
+def test_each_committed_microbatch_enters_exactly_once(fidelity_k):
+    """Sec. 4.2 invariant: every bucket is reduced once under one membership and nothing of
+    the failed replica is retained, also when part of the buckets had already been
+    all-reduced under the old membership (failure during synchronisation)."""
+    off = [0, 3, 5, 8]
+    p = new_proto(4, 2, off=off)
+    out = run_iteration(p, view_oracle, 0, coded(), 4, dying={2: 1}, fidelity_k=fidelity_k)
+    total = p.grad_out * 8
+    assert np.all(total == total[0])
+    assert terms_of(total[0]) == [0, 1, 3, 4, 5, 7, 8, 9]        # no id 2, none twice
+    assert out["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
+
+
+def test_promoted_spare_contributes_its_own_microbatches_after_rewind():
+    """Non-boundary failure with in-place partial sync: the spare's buckets were overwritten
+    by the all-reduce, the rewind brings its own gradients back (boundary walk-through,
+    last paragraph)."""
+    off = [0, 2, 4]
+    p = new_proto(3, 2, off=off)                     # B = 6
+    run_iteration(p, view_oracle, 0, coded(4), 3, dying={2: 0})   # boundary: 2 survivors x 3
+    w = p.world
+    assert w.G_cur == 3 and w.alive() == [0, 1]
+    # make a world with a spare: 5 replicas, B = 10, lose one -> G_cur 3, 3 majors + minor(1)
+    p = new_proto(5, 2, off=off)
+    run_iteration(p, view_oracle, 0, coded(4), 5, dying={4: 1})
+    w = p.world
+    assert (w.G_cur, w.R_cur) == (3, 1) and w.role[:4] == [0, 0, 0, 1]
+    # 6 replicas, B = 12: lose one -> 5 survivors, G_cur 3, 4 majors, no minor, 1 major-spare
+    p = new_proto(6, 2, off=off)
+    run_iteration(p, view_oracle, 0, coded(4), 6, dying={5: 2})
+    w = p.world
+    assert w.role == [0, 0, 0, 0, 2, 4]
+    out = run_iteration(p, view_oracle, 1, coded(4), 6, dying={1: 2}, fidelity_k=1)
+    d = out["decisions"][0]
+    assert not d["at_boundary"] and d["role"][4] == 0
+    total = p.grad_out * 12
+    assert np.all(total == total[0])
+    # ids: r0 {0,6,12}, r2 {2,8,14}, r3 {3,9,15}, promoted r4 {4,10,16}; nothing of r1
+    assert terms_of(total[0]) == [0, 2, 3, 4, 6, 8, 9, 10, 12, 14, 15, 16]
+
+
+def test_constant_gradient_closed_form_and_constant_divisor():
+    """If every microbatch gradient equals c the committed mean is c whatever failed: the
+    divisor stays B = W_init * G_init (Sec. 4.3, Eq. 1; implementation appendix)."""
+    c = np.float32(0.375)
+    g = lambda t, mb: np.full(OFF_RAGGED[-1], c, np.float32)
+    for dtype in (np.float32, np.float64):
+        p = new_proto(8, 4, dtype=dtype)
+        for t, dying in enumerate([None, {3: 2, 6: 2}, None, {0: 1}]):
+            run_iteration(p, view_oracle, t, g, 8, dying=dying)
+            assert np.all(p.grad_out == c)
+
+
+def test_adaptive_policy_commits_fewer_than_B():
+    p = new_proto(4, 2, static=False)
+    out = run_iteration(p, view_oracle, 0, grads(1), 4, dying={2: 1})
+    assert sum(len(v) for v in out["ids"].values()) == 6 < 8
+
+
+def test_restore_after_partial_microbatch_equals_never_started():
+    """Survivors have begun the next microbatch on some tensors when the failure is
+    handled; the rewind to the boundary snapshot leaves no trace of it."""
+    g = grads(5)
+    a = new_proto(4, 2, dtype=np.float32)
+    b = new_proto(4, 2, dtype=np.float32)
+    for p in (a, b):
+        for r in range(4):
+            p.accumulate(r, r, g(0, r))
+        p.snapshot(None)
+    for r in (0, 1, 3):
+        a.accumulate(r, r + 4, g(0, r + 4), 0, 3)     # tensors [0,3) only
+        assert a.world.contributed[r] == 1
+    for p in (a, b):
+        p.on_failure([2])
+        p.restore(None, stale_only=True)
+    for r in (0, 1, 3):
+        assert np.array_equal(a.acc[r].view(np.uint32), b.acc[r].view(np.uint32))
+        assert a.cnt[r] == b.cnt[r] and a.ids[r] == b.ids[r] == [r]
+    for p in (a, b):
+        for r in (0, 1, 3):
+            while p.world.should_contribute(r):
+                k = p.world.contributed[r]
+                p.accumulate(r, r + 4 * k, g(0, r + 4 * k))
+        p.snapshot(None)
+        p.reduce()
+    assert np.array_equal(a.grad_out.view(np.uint32), b.grad_out.view(np.uint32))
+    a.adamw_step(**HP)
+
+
+def test_failure_run_equals_clean_replay_bit_for_bit():
+    """fp32: the committed gradient depends only on the ordered ids inside each
+    contributor's buffer, not on failures, snapshots, in-place reductions or rewinds."""
+    g = grads(7)
+    p = new_proto(8, 4, dtype=np.float32)
+    run_iteration(p, view_oracle, 0, g, 8)
+    out = run_iteration(p, view_oracle, 1, g, 8, dying={3: 2, 6: 2}, fidelity_k=3)
+    got = p.grad_out.copy()
+    assert out["decisions"][0]["restore_mode"] == RESTORE_NONBLOCKING
+    acc = {}
+    for r, ids in out["ids"].items():
+        a = np.float32(0) + g(1, ids[0])
+        for j in ids[1:]:
+            a = a + g(1, j)
+        acc[r] = a
+    rs = sorted(acc)
+    tot = acc[rs[0]].copy()
+    for r in rs[1:]:
+        tot = tot + acc[r]
+    want = tot / np.float32(32)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # another partition of the same ids agrees to rounding only
+    ids = sum(out["ids"].values(), [])
+    one = brute.mean64([g(1, j) for j in ids], 32)
+    assert np.max(np.abs(got - one)) <= 2e-6 * np.max(np.abs(one))
+
+
+def test_bf16_inputs_widen_exactly():
+    g = grads(9, scale=5e-4, bf16=True)
+    p32 = new_proto(4, 2, dtype=np.float32)
+    p64 = new_proto(4, 2, dtype=np.float64)
+    for p in (p32, p64):
+        run_iteration(p, view_oracle, 0, g, 4, dying={1: 1})
+    ref = p64.grad_out
+    assert np.max(np.abs(p32.grad_out - ref)) <= 1e-6 * np.max(np.abs(ref))
+    x = g(0, 0)
+    assert np.all((x.view(np.uint32) & 0xFFFF) == 0)
+
+
+def test_first_microbatch_overwrites_like_zero_then_add():
+    p = new_proto(1, 2, off=[0, 4], dtype=np.float32)
+    p.acc[0][:] = 123.0                                # stale content of the previous iteration
+    g0 = np.array([-0.0, 1.0, -2.0, 0.0], np.float32)
+    p.accumulate(0, 0, g0)
+    assert np.array_equal(p.acc[0], np.array([0.0, 1.0, -2.0, 0.0], np.float32))
+    assert not np.signbit(p.acc[0][0])                 # (+0) + (-0) = +0
+
+
+def test_protocol_violations_are_errors():
+    g = grads(1)
+    p = new_proto(4, 2)
+    for r in range(4):
+        p.accumulate(r, r, g(0, r))
+    p.reduce()
+    with pytest.raises(ProtocolError):                 # only 4 of 8 microbatches inside
+        p.adamw_step(**HP)
+    for r in range(4):
+        p.accumulate(r, r + 4, g(0, r + 4))
+        assert p.accumulate(r, r + 8, g(0, r + 8)) is False     # quota met: dropped
+    with pytest.raises(ProtocolError):                 # reduction predates the last adds
+        p.adamw_step(**HP)
+    p.reduce()
+    p.on_failure([1])
+    with pytest.raises(ProtocolError):                 # epoch moved: everything is stale
+        p.adamw_step(**HP)
+    assert p.reduce() is False                         # quiesced until the restore
+    with pytest.raises(ProtocolError):
+        p.accumulate(1, 99, g(0, 0))                   # dead replica
+    with pytest.raises(ProtocolError):
+        p.accumulate(0, 2, g(0, 0))                    # ids must ascend within a replica
