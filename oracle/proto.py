@@ -92,15 +92,15 @@ class Proto:
         if not w.should_contribute(r):
             return False
         k = w.contributed[r]
-        if self.cur_id[r] is None:
-            if self.fixed_order and self.ids[r] and mb_id <= self.ids[r][-1]:
-                raise ProtocolError("microbatch ids must ascend within a replica")
-            self.cur_id[r] = mb_id
-        elif self.cur_id[r] != mb_id:
-            raise ProtocolError("previous microbatch is incomplete")
+        if self.cur_id[r] is not None:
+            if self.cur_id[r] != mb_id:
+                raise ProtocolError("previous microbatch is incomplete")
+        elif self.fixed_order and self.ids[r] and mb_id <= self.ids[r][-1]:
+            raise ProtocolError("microbatch ids must ascend within a replica")
         for b in range(tb, te):
             if self.cnt[r][b] != k or self.inplace_sum[r][b]:
                 raise ProtocolError("tensor %d of replica %d cannot take this microbatch" % (b, r))
+        self.cur_id[r] = mb_id
         for b in range(tb, te):
             lo, hi = self.off[b], self.off[b + 1]
             gb = np.asarray(g[lo:hi]).astype(self.dtype)       # widening is exact

@@ -1,0 +1,273 @@
+"""ctypes binding of include/recover.h: the same names, argument marshalling only.
+
+Every function takes plain integers for device pointers (`tensor.data_ptr()`) and streams
+(`torch.cuda.current_stream().cuda_stream`) and returns the library's int code; `check`
+turns a negative code into `RecoverError`.  `Shard` is a convenience holder that allocates
+the buffers of one context with PyTorch (device memory and streams only) and forwards to
+the same calls.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librecover.so")
+
+OK, SKIPPED = 0, 1
+ERR_ARG, ERR_STATE, ERR_NO_SURVIVOR, ERR_HIP, ERR_ALIGN, ERR_NO_SNAPSHOT = -1, -2, -3, -4, -5, -6
+F32, BF16 = 0, 1
+ROLE_MAJOR, ROLE_MINOR, ROLE_MAJOR_SPARE, ROLE_MINOR_SPARE, ROLE_DEAD = 0, 1, 2, 3, 4
+RESTORE_SKIP, RESTORE_BLOCKING, RESTORE_NONBLOCKING = 0, 1, 2
+FLAG_ADAPTIVE, FLAG_ANY_ORDER, FLAG_HOST_ONLY = 1, 2, 4
+REDUCE_INPLACE = 1
+MAX_REPLICAS = 64
+
+EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_snapshot", "recover_restore",
+           "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
+           "recover_committed_ids", "recover_last_error", "recover_set_tuning"]
+
+
+class RecoverError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("recover error %d: %s" % (code, msg))
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [("W_init", C.c_int32), ("G_init", C.c_int32), ("n_elems", C.c_int64), ("n_tensors", C.c_int32),
+                ("tensor_offsets", C.POINTER(C.c_int64)), ("acc", C.POINTER(C.c_void_p)),
+                ("snap", C.POINTER(C.c_void_p)), ("grad_out", C.c_void_p), ("param", C.c_void_p),
+                ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p), ("param_bf16", C.c_void_p),
+                ("flags", C.c_uint32)]
+
+
+class Decision(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("at_boundary", "restore_mode", "epoch", "W_cur", "C_cur", "G_ext", "n_bdry",
+                                         "G_cur", "R_cur", "loop_bound", "n_maj", "n_min", "n_ms", "n_mi", "n_bm")] + \
+               [(k, C.POINTER(C.c_int32)) for k in ("role", "target", "contributed", "is_boundary_minor")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("librecover.so is not built; run `python -m paper_2605_11215_amd.build` "
+                               "(there is no CPU implementation of this library)")
+        L = C.CDLL(LIB_PATH)
+        P, I, U32, F, VP = C.c_void_p, C.c_int, C.c_uint32, C.c_float, C.c_void_p
+        L.recover_init.argtypes = [C.POINTER(Config), C.POINTER(P)]
+        L.recover_destroy.argtypes = [P]
+        L.recover_accumulate.argtypes = [P, I, U32, VP, I, I, I, VP]
+        L.recover_snapshot.argtypes = [P, I, I, I, VP]
+        L.recover_restore.argtypes = [P, I, I, VP]
+        L.recover_policy_adjust.argtypes = [P, C.POINTER(C.c_int32), I, C.POINTER(Decision)]
+        L.recover_reduce.argtypes = [P, I, I, U32, VP]
+        L.recover_adamw_step.argtypes = [P, F, F, F, F, F, VP]
+        L.recover_query.argtypes = [P, C.POINTER(Decision)]
+        L.recover_committed_ids.argtypes = [P, I, C.POINTER(U32), I]
+        L.recover_last_error.argtypes = [P]
+        L.recover_last_error.restype = C.c_char_p
+        L.recover_set_tuning.argtypes = [I, I]
+        for name in EXPORTS:
+            if name != "recover_last_error":
+                getattr(L, name).restype = I
+        _lib = L
+    return _lib
+
+
+def recover_last_error(ctx):
+    return lib().recover_last_error(ctx).decode()
+
+
+def check(code, ctx=None):
+    if code < 0:
+        raise RecoverError(code, recover_last_error(ctx))
+    return code
+
+
+def recover_init(W_init, G_init, tensor_offsets, acc, snap, grad_out, param, exp_avg, exp_avg_sq, param_bf16=0,
+                 flags=0):
+    """acc / snap: sequences of W_init device addresses (snap may be None).  Returns (code, ctx)."""
+    T = len(tensor_offsets) - 1
+    off = (C.c_int64 * (T + 1))(*tensor_offsets)
+    cfg = Config()
+    cfg.W_init, cfg.G_init, cfg.n_elems, cfg.n_tensors = W_init, G_init, tensor_offsets[-1], T
+    cfg.tensor_offsets = off
+    keep = [off]
+    if acc is not None:
+        a = (C.c_void_p * len(acc))(*acc)
+        cfg.acc = a
+        keep.append(a)
+    if snap is not None:
+        s = (C.c_void_p * len(snap))(*snap)
+        cfg.snap = s
+        keep.append(s)
+    cfg.grad_out, cfg.param, cfg.exp_avg, cfg.exp_avg_sq = grad_out or None, param or None, exp_avg or None, exp_avg_sq or None
+    cfg.param_bf16 = param_bf16 or None
+    cfg.flags = flags
+    ctx = C.c_void_p()
+    code = lib().recover_init(C.byref(cfg), C.byref(ctx))
+    return code, ctx
+
+
+def recover_destroy(ctx):
+    return lib().recover_destroy(ctx)
+
+
+def recover_accumulate(ctx, replica, global_mb_id, grad, dtype, tensor_begin, tensor_end, stream=0):
+    return lib().recover_accumulate(ctx, replica, global_mb_id, grad or None, dtype, tensor_begin, tensor_end,
+                                    stream or None)
+
+
+def recover_snapshot(ctx, replica, tensor_begin, tensor_end, stream=0):
+    return lib().recover_snapshot(ctx, replica, tensor_begin, tensor_end, stream or None)
+
+
+def recover_restore(ctx, replica, stale_only, stream=0):
+    return lib().recover_restore(ctx, replica, int(stale_only), stream or None)
+
+
+def _decision(W):
+    d = Decision()
+    arrs = [(C.c_int32 * W)() for _ in range(4)]
+    d.role, d.target, d.contributed, d.is_boundary_minor = [C.cast(a, C.POINTER(C.c_int32)) for a in arrs]
+    return d, arrs
+
+
+def _decision_dict(d, arrs):
+    out = {k: getattr(d, k) for k, _ in Decision._fields_[:15]}
+    for k, a in zip(("role", "target", "contributed", "is_boundary_minor"), arrs):
+        out[k] = list(a)
+    return out
+
+
+def recover_policy_adjust(ctx, failed, W_init):
+    """Returns (code, decision dict)."""
+    d, arrs = _decision(W_init)
+    f = (C.c_int32 * max(1, len(failed)))(*failed)
+    code = lib().recover_policy_adjust(ctx, f, len(failed), C.byref(d))
+    return code, _decision_dict(d, arrs)
+
+
+def recover_reduce(ctx, tensor_begin, tensor_end, flags=0, stream=0):
+    return lib().recover_reduce(ctx, tensor_begin, tensor_end, flags, stream or None)
+
+
+def recover_adamw_step(ctx, lr, beta1, beta2, eps, weight_decay, stream=0):
+    return lib().recover_adamw_step(ctx, lr, beta1, beta2, eps, weight_decay, stream or None)
+
+
+def recover_query(ctx, W_init):
+    d, arrs = _decision(W_init)
+    code = lib().recover_query(ctx, C.byref(d))
+    return code, _decision_dict(d, arrs)
+
+
+def recover_committed_ids(ctx, replica, cap=4096):
+    buf = (C.c_uint32 * cap)()
+    n = lib().recover_committed_ids(ctx, replica, buf, cap)
+    return n, list(buf[:max(0, min(n, cap))])
+
+
+def recover_set_tuning(key, value):
+    return lib().recover_set_tuning(key, value)
+
+
+class Shard:
+    """Buffers of one context allocated with PyTorch on `device`, plus the calls on it.
+
+    Holds: acc[r], snap[r] (optional), grad_out, param, exp_avg, exp_avg_sq (all fp32, flat).
+    Methods mirror the C calls, raise RecoverError on negative codes, and use torch's
+    current stream."""
+
+    def __init__(self, W_init, G_init, tensor_offsets, device="cuda:0", snapshots=True, flags=0, param_bf16=False,
+                 host_only=False):
+        import torch
+        self.torch = torch
+        self.W, self.G = W_init, G_init
+        self.off = [int(x) for x in tensor_offsets]
+        self.N, self.T = self.off[-1], len(self.off) - 1
+        self.host_only = host_only
+        if host_only:
+            flags |= FLAG_HOST_ONLY
+            code, self.ctx = recover_init(W_init, G_init, self.off, None, None, 0, 0, 0, 0, 0, flags)
+        else:
+            z = lambda dt=torch.float32: torch.zeros(max(self.N, 4), dtype=dt, device=device)
+            self.acc = [z() for _ in range(W_init)]
+            self.snap = [z() for _ in range(W_init)] if snapshots else None
+            self.grad_out, self.param, self.exp_avg, self.exp_avg_sq = z(), z(), z(), z()
+            self.param_bf16 = z(torch.bfloat16) if param_bf16 else None
+            code, self.ctx = recover_init(
+                W_init, G_init, self.off, [t.data_ptr() for t in self.acc],
+                [t.data_ptr() for t in self.snap] if snapshots else None, self.grad_out.data_ptr(),
+                self.param.data_ptr(), self.exp_avg.data_ptr(), self.exp_avg_sq.data_ptr(),
+                self.param_bf16.data_ptr() if param_bf16 else 0, flags)
+        if code < 0:
+            raise RecoverError(code, recover_last_error(None))
+
+    def close(self):
+        if self.ctx:
+            recover_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self):
+        return 0 if self.host_only else self.torch.cuda.current_stream().cuda_stream
+
+    def accumulate(self, r, mb_id, g, tb=0, te=None):
+        """g: a flat torch tensor on the device (float32 or bfloat16), or None on a host-only context.
+        Returns False if the quota was already met."""
+        te = self.T if te is None else te
+        if self.host_only:
+            ptr, dt = 0, F32
+        else:
+            dt = BF16 if g.dtype == self.torch.bfloat16 else F32
+            assert g.is_contiguous() and g.numel() >= self.N
+            ptr = g.data_ptr()
+        return check(recover_accumulate(self.ctx, r, mb_id, ptr, dt, tb, te, self._stream()), self.ctx) == OK
+
+    def snapshot(self, r=None, tb=0, te=None):
+        te = self.T if te is None else te
+        check(recover_snapshot(self.ctx, -1 if r is None else r, tb, te, self._stream()), self.ctx)
+
+    def restore(self, r=None, stale_only=True):
+        check(recover_restore(self.ctx, -1 if r is None else r, stale_only, self._stream()), self.ctx)
+
+    def on_failure(self, failed):
+        code, d = recover_policy_adjust(self.ctx, list(failed), self.W)
+        check(code, self.ctx)
+        return d
+
+    def advance(self):
+        code, d = recover_policy_adjust(self.ctx, [], self.W)
+        check(code, self.ctx)
+        return d
+
+    def reduce(self, tb=0, te=None, inplace=False):
+        te = self.T if te is None else te
+        return check(recover_reduce(self.ctx, tb, te, REDUCE_INPLACE if inplace else 0, self._stream()), self.ctx) == OK
+
+    def adamw_step(self, lr, beta1, beta2, eps, weight_decay):
+        check(recover_adamw_step(self.ctx, lr, beta1, beta2, eps, weight_decay, self._stream()), self.ctx)
+
+    def query(self):
+        code, d = recover_query(self.ctx, self.W)
+        check(code, self.ctx)
+        return d
+
+    def committed_ids_by_replica(self):
+        q = self.query()
+        out = {}
+        for r in range(self.W):
+            if q["role"][r] in (ROLE_MAJOR, ROLE_MINOR):
+                n, ids = recover_committed_ids(self.ctx, r)
+                out[r] = ids
+        return out

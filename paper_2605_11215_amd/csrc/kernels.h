@@ -1,0 +1,36 @@
+// Internal launch interface between the host bookkeeping (recover_host.cpp) and the gfx950
+// kernels (kernels.hip).  All pointers are device pointers; [begin, end) are element indices
+// into flat buffers; every launcher returns a hipError_t and never synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace recover {
+
+constexpr int kMaxReplicas = 64;
+
+struct Tuning {
+  int vecs_per_thread = 4;  // 128-bit vectors each lane keeps in flight per stream
+  int nontemporal = 1;      // streaming cache hints on loads and stores
+  int grid_cap = 0;         // 0: one tile per workgroup; else grid-stride over at most this many
+};
+Tuning &tuning();
+
+struct ReduceArgs {
+  const float *src[kMaxReplicas];  // contributors, ascending replica index
+  float *sum_dst[kMaxReplicas];    // buffers that also receive the undivided sum (in-place mode)
+  int n_src;
+  int n_sum_dst;
+  float *out;
+  float divisor;
+};
+
+hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bool first, size_t begin,
+                             size_t end, hipStream_t s);
+hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s);
+hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s);
+hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n,
+                        float decay_mul, float beta1, float one_minus_beta1, float beta2,
+                        float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps, hipStream_t s);
+
+}  // namespace recover

@@ -1,0 +1,399 @@
+// gfx950 kernels of the gradient path.  Every step is an elementwise stream over flat fp32
+// buffers, bound by HBM bandwidth, so the design is the same everywhere: one 128-bit load or
+// store per lane per access (a wavefront moves 1 KiB of consecutive bytes per instruction),
+// several independent vectors in flight per lane before the first use, 64-bit element indices
+// (a shard can exceed 2^32 bytes), no LDS (no element is used twice) and no atomics (the sums
+// have a fixed order).  Ranges that do not start or end on a 16-byte boundary get their ragged
+// ends from a few lanes of workgroup 0.
+#include "kernels.h"
+
+namespace recover {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+
+Tuning &tuning() {
+  static Tuning t;
+  return t;
+}
+
+// A range [begin, end) of elements split into a ragged head, nvec aligned 4-element vectors
+// starting at element vbegin, and a ragged tail.
+struct Span {
+  size_t begin, end, vbegin, nvec;
+};
+
+static Span make_span(size_t begin, size_t end) {
+  Span s;
+  s.begin = begin;
+  s.end = end;
+  size_t vb = (begin + 3) & ~size_t(3);
+  if (vb > end) vb = end;
+  s.vbegin = vb;
+  s.nvec = (end - vb) / 4;
+  return s;
+}
+
+// Element index of the k-th ragged element (head first, then tail), or end if k is past them.
+__device__ inline size_t ragged_index(const Span &sp, unsigned k) {
+  size_t head = sp.vbegin - sp.begin;
+  if (k < head) return sp.begin + k;
+  size_t i = sp.vbegin + sp.nvec * 4 + (k - head);
+  return i < sp.end ? i : sp.end;
+}
+
+template <bool NT, typename T>
+__device__ inline T ld(const T *p) {
+  if (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT, typename T>
+__device__ inline void st(T *p, T v) {
+  if (NT)
+    __builtin_nontemporal_store(v, p);
+  else
+    *p = v;
+}
+
+__device__ inline float bf16_to_f32(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
+
+// Four gradient elements of vector i, widened to fp32.
+template <bool NT>
+__device__ inline f32x4 load_grad(const float *g, size_t i) {
+  return ld<NT>(reinterpret_cast<const f32x4 *>(g) + i);
+}
+template <bool NT>
+__device__ inline f32x4 load_grad(const uint16_t *g, size_t i) {
+  u32x2 w = ld<NT>(reinterpret_cast<const u32x2 *>(g) + i);
+  f32x4 r;
+  r.x = __builtin_bit_cast(float, w.x << 16);
+  r.y = __builtin_bit_cast(float, w.x & 0xFFFF0000u);
+  r.z = __builtin_bit_cast(float, w.y << 16);
+  r.w = __builtin_bit_cast(float, w.y & 0xFFFF0000u);
+  return r;
+}
+__device__ inline float load_grad1(const float *g, size_t i) { return g[i]; }
+__device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to_f32(g[i]); }
+
+// ---------------------------------------------------------------------------------------------
+// accumulate: acc[i] = acc[i] + widen(g[i]);  FIRST: acc[i] = (+0) + widen(g[i])
+// ---------------------------------------------------------------------------------------------
+template <typename G, int U, bool NT, bool FIRST>
+__global__ __launch_bounds__(kThreads) void k_accumulate(float *__restrict__ acc, const G *__restrict__ g,
+                                                         Span sp, size_t ntiles) {
+  f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
+  const G *gv = g + sp.vbegin;
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    f32x4 x[U], a[U];
+    if (base + size_t(kThreads) * (U - 1) < sp.nvec) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[u] = load_grad<NT>(gv, base + size_t(kThreads) * u);
+      if (!FIRST) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = ld<NT>(a4 + base + size_t(kThreads) * u);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) st<NT>(a4 + base + size_t(kThreads) * u, (FIRST ? zero : a[u]) + x[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t i = base + size_t(kThreads) * u;
+        if (i < sp.nvec) {
+          f32x4 xv = load_grad<NT>(gv, i);
+          f32x4 av = FIRST ? zero : ld<NT>(a4 + i);
+          st<NT>(a4 + i, av + xv);
+        }
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 8) {
+    const size_t i = ragged_index(sp, threadIdx.x);
+    if (i < sp.end) acc[i] = (FIRST ? 0.f : acc[i]) + load_grad1(g, i);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// copy (snapshot and restore): dst[i] = src[i]
+// ---------------------------------------------------------------------------------------------
+template <int U, bool NT>
+__global__ __launch_bounds__(kThreads) void k_copy(float *__restrict__ dst, const float *__restrict__ src, Span sp,
+                                                   size_t ntiles) {
+  f32x4 *d4 = reinterpret_cast<f32x4 *>(dst + sp.vbegin);
+  const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + sp.vbegin);
+  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    f32x4 x[U];
+    if (base + size_t(kThreads) * (U - 1) < sp.nvec) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[u] = ld<NT>(s4 + base + size_t(kThreads) * u);
+#pragma unroll
+      for (int u = 0; u < U; ++u) st<NT>(d4 + base + size_t(kThreads) * u, x[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t i = base + size_t(kThreads) * u;
+        if (i < sp.nvec) st<NT>(d4 + i, ld<NT>(s4 + i));
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 8) {
+    const size_t i = ragged_index(sp, threadIdx.x);
+    if (i < sp.end) dst[i] = src[i];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// reduce: out[i] = ((src0[i] + src1[i]) + ...) / divisor, ascending contributor order; in-place mode
+// also stores the undivided sum to every sum_dst buffer.  Contributor loads are issued eight at a
+// time; the adds stay strictly left to right.
+// ---------------------------------------------------------------------------------------------
+constexpr int kReduceBatch = 8;
+
+template <bool NT>
+__device__ inline f32x4 reduce_vec(const ReduceArgs &a, size_t vec_index, size_t vbegin) {
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  for (int r0 = 0; r0 < a.n_src; r0 += kReduceBatch) {
+    f32x4 t[kReduceBatch];
+#pragma unroll
+    for (int j = 0; j < kReduceBatch; ++j)
+      if (r0 + j < a.n_src) t[j] = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r0 + j] + vbegin) + vec_index);
+#pragma unroll
+    for (int j = 0; j < kReduceBatch; ++j)
+      if (r0 + j < a.n_src) sum = (r0 + j == 0) ? t[j] : sum + t[j];
+  }
+  return sum;
+}
+
+template <int U, bool NT, bool INPLACE>
+__global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size_t ntiles) {
+  f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
+  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = base + size_t(kThreads) * u;
+      if (i < sp.nvec) {
+        f32x4 sum = reduce_vec<NT>(a, i, sp.vbegin);
+        if (INPLACE) {
+          for (int d = 0; d < a.n_sum_dst; ++d) st<NT>(reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + i, sum);
+        }
+        f32x4 q;
+        q.x = sum.x / a.divisor;
+        q.y = sum.y / a.divisor;
+        q.z = sum.z / a.divisor;
+        q.w = sum.w / a.divisor;
+        st<NT>(o4 + i, q);
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 8) {
+    const size_t i = ragged_index(sp, threadIdx.x);
+    if (i < sp.end) {
+      float sum = 0.f;
+      for (int r = 0; r < a.n_src; ++r) sum = (r == 0) ? a.src[r][i] : sum + a.src[r][i];
+      if (INPLACE)
+        for (int d = 0; d < a.n_sum_dst; ++d) a.sum_dst[d][i] = sum;
+      a.out[i] = sum / a.divisor;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// AdamW (decoupled weight decay), fp32 state:
+//   p *= decay_mul;  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g g;
+//   p -= step_size * m / (sqrt(v) * inv_sqrt_bc2 + eps)
+// with decay_mul = 1 - lr wd, step_size = lr / (1 - b1^t), inv_sqrt_bc2 = 1 / sqrt(1 - b2^t)
+// prepared in double on the host.
+// ---------------------------------------------------------------------------------------------
+struct AdamArgs {
+  float decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps;
+};
+
+__device__ inline void adam1(float &p, float &m, float &v, float g, const AdamArgs &h) {
+  m = h.beta1 * m + h.one_minus_beta1 * g;
+  v = h.beta2 * v + h.one_minus_beta2 * (g * g);
+  float denom = sqrtf(v) * h.inv_sqrt_bc2 + h.eps;
+  p = p * h.decay_mul - h.step_size * (m / denom);
+}
+
+__device__ inline uint32_t f32_to_bf16_rne(float x) {
+  uint32_t b = __builtin_bit_cast(uint32_t, x);
+  return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+template <int U, bool NT, bool BF16OUT>
+__global__ __launch_bounds__(kThreads) void k_adamw(float *__restrict__ p, float *__restrict__ m,
+                                                    float *__restrict__ v, const float *__restrict__ g,
+                                                    uint16_t *__restrict__ pb, size_t n, AdamArgs h, size_t ntiles) {
+  const size_t nvec = n / 4;
+  f32x4 *p4 = reinterpret_cast<f32x4 *>(p), *m4 = reinterpret_cast<f32x4 *>(m), *v4 = reinterpret_cast<f32x4 *>(v);
+  const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
+  u32x2 *b2 = reinterpret_cast<u32x2 *>(pb);
+  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    f32x4 gv[U], pv[U], mv[U], vv[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = base + size_t(kThreads) * u;
+      ok[u] = i < nvec;
+      if (ok[u]) {
+        gv[u] = ld<NT>(g4 + i);
+        pv[u] = ld<NT>(p4 + i);
+        mv[u] = ld<NT>(m4 + i);
+        vv[u] = ld<NT>(v4 + i);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = base + size_t(kThreads) * u;
+      if (ok[u]) {
+#pragma unroll
+        for (int l = 0; l < 4; ++l) {
+          float pp = pv[u][l], mm = mv[u][l], v1 = vv[u][l];
+          adam1(pp, mm, v1, gv[u][l], h);
+          pv[u][l] = pp;
+          mv[u][l] = mm;
+          vv[u][l] = v1;
+        }
+        st<NT>(p4 + i, pv[u]);
+        st<NT>(m4 + i, mv[u]);
+        st<NT>(v4 + i, vv[u]);
+        if (BF16OUT) {
+          u32x2 w;
+          w.x = f32_to_bf16_rne(pv[u].x) | (f32_to_bf16_rne(pv[u].y) << 16);
+          w.y = f32_to_bf16_rne(pv[u].z) | (f32_to_bf16_rne(pv[u].w) << 16);
+          st<NT>(b2 + i, w);
+        }
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 4) {
+    const size_t i = nvec * 4 + threadIdx.x;
+    if (i < n) {
+      float pp = p[i], mm = m[i], vv = v[i];
+      adam1(pp, mm, vv, g[i], h);
+      p[i] = pp;
+      m[i] = mm;
+      v[i] = vv;
+      if (BF16OUT) pb[i] = (uint16_t)f32_to_bf16_rne(pp);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+static bool grid_for(size_t nvec, int U, unsigned *grid, size_t *ntiles) {
+  size_t tiles = (nvec + size_t(kThreads) * U - 1) / (size_t(kThreads) * U);
+  *ntiles = tiles;
+  size_t g = tiles ? tiles : 1;
+  int cap = tuning().grid_cap;
+  if (cap > 0 && g > size_t(cap)) g = size_t(cap);
+  if (g > 0x7FFFFFFFull) return false;
+  *grid = (unsigned)g;
+  return true;
+}
+
+#define RECOVER_DISPATCH_U_NT(U_, NT_, CALL)                    \
+  do {                                                          \
+    if (NT_) {                                                  \
+      switch (U_) {                                             \
+        case 1: { constexpr int U = 1; constexpr bool NT = true; CALL; } break;  \
+        case 2: { constexpr int U = 2; constexpr bool NT = true; CALL; } break;  \
+        case 8: { constexpr int U = 8; constexpr bool NT = true; CALL; } break;  \
+        default: { constexpr int U = 4; constexpr bool NT = true; CALL; } break; \
+      }                                                         \
+    } else {                                                    \
+      switch (U_) {                                             \
+        case 1: { constexpr int U = 1; constexpr bool NT = false; CALL; } break;  \
+        case 2: { constexpr int U = 2; constexpr bool NT = false; CALL; } break;  \
+        case 8: { constexpr int U = 8; constexpr bool NT = false; CALL; } break;  \
+        default: { constexpr int U = 4; constexpr bool NT = false; CALL; } break; \
+      }                                                         \
+    }                                                           \
+  } while (0)
+
+hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bool first, size_t begin, size_t end,
+                             hipStream_t s) {
+  if (begin >= end) return hipSuccess;
+  Span sp = make_span(begin, end);
+  const int Uv = tuning().vecs_per_thread;
+  unsigned grid;
+  size_t ntiles;
+  if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  if (grad_is_bf16) {
+    const uint16_t *g = static_cast<const uint16_t *>(grad);
+    RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+      if (first)
+        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+      else
+        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+    });
+  } else {
+    const float *g = static_cast<const float *>(grad);
+    RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+      if (first)
+        hipLaunchKernelGGL((k_accumulate<float, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+      else
+        hipLaunchKernelGGL((k_accumulate<float, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+    });
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s) {
+  if (begin >= end) return hipSuccess;
+  Span sp = make_span(begin, end);
+  const int Uv = tuning().vecs_per_thread;
+  unsigned grid;
+  size_t ntiles;
+  if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+    hipLaunchKernelGGL((k_copy<U, NT>), dim3(grid), dim3(kThreads), 0, s, dst, src, sp, ntiles);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s) {
+  if (begin >= end) return hipSuccess;
+  Span sp = make_span(begin, end);
+  int Uv = tuning().vecs_per_thread > 2 ? 2 : tuning().vecs_per_thread;
+  unsigned grid;
+  size_t ntiles;
+  if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  const bool inplace = a.n_sum_dst > 0;
+  RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+    constexpr int UR = U > 2 ? 2 : U;
+    if (inplace)
+      hipLaunchKernelGGL((k_reduce<UR, NT, true>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
+    else
+      hipLaunchKernelGGL((k_reduce<UR, NT, false>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, float decay_mul,
+                        float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float step_size,
+                        float inv_sqrt_bc2, float eps, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
+  int Uv = tuning().vecs_per_thread > 2 ? 2 : tuning().vecs_per_thread;
+  unsigned grid;
+  size_t ntiles;
+  if (!grid_for(n / 4, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+    constexpr int UA = U > 2 ? 2 : U;
+    if (p_bf16)
+      hipLaunchKernelGGL((k_adamw<UA, NT, true>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+    else
+      hipLaunchKernelGGL((k_adamw<UA, NT, false>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+  });
+  return hipGetLastError();
+}
+
+}  // namespace recover

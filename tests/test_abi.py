@@ -1,0 +1,219 @@
+"""The C-ABI library without a GPU: it loads, exports what include/recover.h declares, and its
+host logic (policy, bookkeeping, error returns) agrees with the oracle call by call on
+host-only contexts (no kernel runs; nothing is computed).  CPU only."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.proto import Proto, ProtocolError
+from oracle import policy as OP
+from paper_2605_11215_amd import binding as B
+from tests.driver import run_iteration, view_oracle, HP
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "recover.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(recover_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    names = declared_functions()
+    for must in ("recover_init", "recover_accumulate", "recover_snapshot", "recover_restore",
+                 "recover_policy_adjust", "recover_reduce", "recover_adamw_step"):
+        assert must in names
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_synth_library_exports():
+    from paper_2605_11215_amd import synth
+    assert hasattr(ctypes.CDLL(synth.LIB_PATH), "synth_fill")
+
+
+def test_device_calls_fail_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    code, ctx = B.recover_init(2, 2, [0, 8], [16, 32], None, 16, 16, 16, 16)
+    assert code == B.ERR_HIP and "no CPU path" in B.recover_last_error(None)
+
+
+def test_argument_errors():
+    assert B.recover_init(0, 2, [0, 8], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
+    assert B.recover_init(65, 2, [0, 8], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
+    assert B.recover_init(2, 2, [0, 8, 4], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
+    assert B.recover_init(2, 2, [0, 8], [16, 24 + 4], None, 16, 16, 16, 16)[0] == B.ERR_ALIGN
+    s = B.Shard(2, 2, [0, 8, 16], host_only=True)
+    assert B.recover_accumulate(s.ctx, 2, 0, 0, B.F32, 0, 2) == B.ERR_ARG
+    assert B.recover_accumulate(s.ctx, 0, 0, 0, 7, 0, 2) == B.ERR_ARG
+    assert B.recover_accumulate(s.ctx, 0, 0, 0, B.F32, 1, 3) == B.ERR_ARG
+    assert B.recover_reduce(s.ctx, 0, 2, 8) == B.ERR_ARG
+    assert B.recover_adamw_step(s.ctx, 1e-3, 1.5, 0.95, 1e-8, 0.1) == B.ERR_ARG
+    assert B.recover_policy_adjust(s.ctx, [0, 1], 2)[0] == B.ERR_NO_SURVIVOR
+    assert B.recover_policy_adjust(s.ctx, [5], 2)[0] == B.ERR_ARG
+    assert B.recover_set_tuning(0, 3) == B.ERR_ARG and B.recover_set_tuning(0, 4) == B.OK
+    assert B.recover_query(s.ctx, 2)[1]["target"] == [2, 2]        # unchanged by the failed calls
+
+
+INT_KEYS = ("at_boundary", "restore_mode", "epoch", "W_cur", "C_cur", "G_ext", "n_bdry", "G_cur", "R_cur",
+            "loop_bound", "n_maj", "n_min", "n_ms", "n_mi", "n_bm", "role", "target", "contributed",
+            "is_boundary_minor")
+
+
+def same_decision(a, b):
+    for k in INT_KEYS:
+        assert a[k] == b[k], (k, a[k], b[k])
+
+
+def view_hip(s):
+    q = s.query()
+    return dict(alive=[r for r in range(s.W) if q["role"][r] != B.ROLE_DEAD], target=q["target"],
+                contributed=q["contributed"], loop_bound=q["loop_bound"], role=q["role"], epoch=q["epoch"])
+
+
+def test_policy_bit_exact_against_oracle_on_sweeps():
+    """Every (W <= 6, G <= 3) and every sequence of three failure sets of size <= 2, plus the
+    64-replica attrition: each decision record equals the oracle's field by field."""
+    n = 0
+    for W in range(1, 7):
+        for G in range(1, 4):
+            sets = [()] + [(a,) for a in range(W)] + list(itertools.combinations(range(W), 2))
+            for seq in itertools.product(sets, repeat=3):
+                o = OP.World(W, G)
+                s = B.Shard(W, G, [0, 4], host_only=True)
+                for picks in seq:
+                    for r in o.alive():                       # everybody reaches the quota
+                        while o.contributed[r] < o.target[r]:
+                            o.contributed[r] += 1
+                            assert s.accumulate(r, r + W * o.contributed[r], None)
+                        assert not s.accumulate(r, 10 ** 6, None)
+                    alive = o.alive()
+                    failed = sorted({alive[k % len(alive)] for k in picks})
+                    if len(failed) == len(alive):
+                        assert B.recover_policy_adjust(s.ctx, failed, W)[0] == B.ERR_NO_SURVIVOR
+                        break
+                    if failed:
+                        same_decision(s.on_failure(failed), o.on_failure(failed))
+                        s.restore()
+                        for r in o.alive():
+                            while o.contributed[r] < o.target[r]:
+                                o.contributed[r] += 1
+                                assert s.accumulate(r, r + W * o.contributed[r], None)
+                    assert s.reduce()
+                    s.adamw_step(**HP)
+                    o.commit()
+                    same_decision(s.advance(), o.advance())
+                    n += 1
+                s.close()
+    assert n > 3000
+
+
+@pytest.mark.parametrize("static", [True, False])
+def test_protocol_bookkeeping_matches_oracle_call_by_call(static):
+    """Random schedules (failures at random offsets, partial in-place synchronisation, snapshots
+    at every boundary) through the shared driver: same decisions, same committed ids."""
+    rng = np.random.default_rng(5)
+    off = [0, 3, 8, 8, 20]
+    g = np.zeros(off[-1], np.float32)
+    for trial in range(60):
+        W, G = int(rng.integers(2, 9)), int(rng.integers(1, 5))
+        o = Proto(W, G, off, dtype=np.float32, static=static)
+        o.set_state(g)
+        s = B.Shard(W, G, off, host_only=True, flags=0 if static else B.FLAG_ADAPTIVE)
+
+        class HostOnly:                                    # adapter: the driver passes arrays
+            def __getattr__(self, k):
+                return getattr(s, k)
+
+            def accumulate(self, r, mb, grad, tb=0, te=None):
+                return s.accumulate(r, mb, None, tb, te)
+
+        h = HostOnly()
+        for t in range(5):
+            alive = o.world.alive()
+            if len(alive) == 1:
+                break
+            nf = int(rng.integers(0, min(3, len(alive))))
+            dying = {int(r): int(rng.integers(0, max(1, o.world.target[r]) + 1))
+                     for r in rng.choice(alive, nf, replace=False)}
+            kw = dict(dying=dying, fidelity_k=int(rng.integers(0, 5)), snapshot_every=bool(rng.integers(0, 2)))
+            a = run_iteration(o, view_oracle, t, lambda t, mb: g, W, **kw)
+            b = run_iteration(h, view_hip, t, lambda t, mb: None, W, **kw)
+            assert a["ids"] == b["ids"]
+            assert len(a["decisions"]) == len(b["decisions"])
+            for x, y in zip(a["decisions"], b["decisions"]):
+                same_decision(y, x)
+        s.close()
+
+
+def test_state_errors_match_the_oracle():
+    off = [0, 4, 8]
+    g = np.zeros(8, np.float32)
+    o = Proto(4, 2, off, dtype=np.float32)
+    o.set_state(g)
+    s = B.Shard(4, 2, off, host_only=True)
+
+    def both(name, *args, **kw):
+        """Call on both; return (oracle raised?, library code)."""
+        try:
+            getattr(o, name)(*args, **kw)
+            raised = False
+        except ProtocolError:
+            raised = True
+        return raised
+
+    for r in range(4):
+        o.accumulate(r, r, g)
+        assert s.accumulate(r, r, None)
+    o.reduce()
+    s.reduce()
+    assert both("adamw_step", **HP) and B.recover_adamw_step(s.ctx, 1e-3, 0.9, 0.95, 1e-8, 0.1) == B.ERR_STATE
+    # partial microbatch, then a different id
+    o.accumulate(0, 4, g, 0, 1)
+    assert s.accumulate(0, 4, None, 0, 1)
+    assert both("accumulate", 0, 8, g, 1, 2) and B.recover_accumulate(s.ctx, 0, 8, 0, 0, 1, 2) == B.ERR_STATE
+    assert both("accumulate", 0, 4, g, 0, 1) and B.recover_accumulate(s.ctx, 0, 4, 0, 0, 0, 1) == B.ERR_STATE
+    o.accumulate(0, 4, g, 1, 2)
+    assert s.accumulate(0, 4, None, 1, 2)
+    assert both("accumulate", 1, 0, g) and B.recover_accumulate(s.ctx, 1, 0, 0, 0, 0, 2) == B.ERR_ARG
+    # in-place sum blocks snapshot, accumulate and a second reduction until the rewind
+    o.snapshot(None)
+    s.snapshot()
+    o.reduce(0, 1, inplace=True)
+    s.reduce(0, 1, inplace=True)
+    assert both("snapshot", 1, 0, 1) and B.recover_snapshot(s.ctx, 1, 0, 1) == B.ERR_STATE
+    assert both("reduce", 0, 2) and B.recover_reduce(s.ctx, 0, 2, 0) == B.ERR_STATE
+    assert both("accumulate", 1, 5, g) and B.recover_accumulate(s.ctx, 1, 5, 0, 0, 0, 2) == B.ERR_STATE
+    o.on_failure([3])
+    s.on_failure([3])
+    assert o.reduce(1, 2) is False and B.recover_reduce(s.ctx, 1, 2, 0) == B.SKIPPED
+    assert both("accumulate", 3, 7, g) and B.recover_accumulate(s.ctx, 3, 7, 0, 0, 0, 2) == B.ERR_STATE
+    assert both("adamw_step", **HP) and B.recover_adamw_step(s.ctx, 1e-3, 0.9, 0.95, 1e-8, 0.1) == B.ERR_STATE
+    o.restore(None)
+    s.restore()
+    assert view_hip(s)["contributed"] == list(o.world.contributed)
+    assert view_hip(s)["target"] == list(o.world.target)
+    # rewind that would split a replica across two microbatch counts
+    o2 = Proto(2, 3, off, dtype=np.float32)
+    s2 = B.Shard(2, 3, off, host_only=True)
+    o2.accumulate(0, 0, g)
+    s2.accumulate(0, 0, None)
+    o2.snapshot(0, 0, 1)
+    s2.snapshot(0, 0, 1)
+    o2.accumulate(0, 2, g)
+    s2.accumulate(0, 2, None)
+    with pytest.raises(ProtocolError):
+        o2.restore(0, stale_only=False)
+    assert B.recover_restore(s2.ctx, 0, 0) == B.ERR_STATE
+    # no snapshot buffers
+    code, ctx = B.recover_init(2, 2, [0, 8], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)
+    assert code == 0

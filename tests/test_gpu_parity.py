@@ -1,0 +1,256 @@
+"""GPU parity tests proper: the HIP library, called through the C ABI, against the CPU
+oracle element by element on the same seeded inputs.
+
+Bars: integers (quotas, roles, ids) bit-exact; the iteration gradient bit-exact against the
+oracle evaluated in fp32 (the precision the paper accumulates and synchronises in: adds and
+one divide, same order) and within 1e-6 max-norm relative error of the fp64 oracle (1e-2
+when bf16 gradients are compared with the unrounded fp32 samples); AdamW state within 1e-6
+max-norm relative error of the fp64 oracle fed the same fp32 gradient."""
+import numpy as np
+import pytest
+
+from oracle.proto import Proto
+from oracle import adamw as oracle_adamw
+from paper_2605_11215_amd import binding as B
+from paper_2605_11215_amd import synth
+from paper_2605_11215_amd.synth import reference_np as S
+from tests.driver import run_iteration, view_oracle, HP
+from tests.gpu_harness import HipEngine, view_hip, max_rel, bits_equal
+
+pytestmark = pytest.mark.gpu
+
+# lengths 1, 3, 5, 1023, 0, 4099, 20000, 7: ragged ends, an empty tensor, several 4096-element tiles
+OFF = [0, 1, 4, 9, 1032, 1032, 5131, 25131, 25138]
+
+
+def torch_():
+    import torch
+    return torch
+
+
+def hp32():
+    return {k: float(np.float32(v)) for k, v in HP.items()}
+
+
+def test_synth_device_stream_equals_numpy_bits():
+    torch = torch_()
+    n, start = 300003, 5
+    for kind, bf16 in [(S.KIND_NORMAL, False), (S.KIND_NORMAL, True), (S.KIND_STUDENT_T3, False),
+                       (S.KIND_STUDENT_T3, True)]:
+        out = torch.empty(n, dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+        synth.fill_device(out, 1, S.TAG_GRAD, 9, 2, 1e-3, kind, start=start)
+        want = S.fill(n, 1, S.TAG_GRAD, 9, 2, 1e-3, kind, start=start)
+        if bf16:
+            got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, S.f32_to_bf16_bits(want))
+        else:
+            assert bits_equal(out.cpu().numpy(), want)
+    far = torch.empty(1000, dtype=torch.float32, device="cuda")
+    synth.fill_device(far, 1, S.TAG_GRAD, 63, 3, 1e-3, start=1978662912 - 1000)
+    assert bits_equal(far.cpu().numpy(), S.fill(1000, 1, S.TAG_GRAD, 63, 3, 1e-3, start=1978662912 - 1000))
+
+
+def make_pair(W, G, off, bf16, seed, flags=0):
+    torch = torch_()
+    p0 = S.fill(off[-1], seed, S.TAG_PARAM, 0, 0, 0.02)
+    o32 = Proto(W, G, off, dtype=np.float32, static=not (flags & B.FLAG_ADAPTIVE))
+    o32.set_state(p0)
+    s = B.Shard(W, G, off, flags=flags, param_bf16=True)
+    s.param[:off[-1]].copy_(torch.from_numpy(p0))
+    return o32, s, HipEngine(s, bf16)
+
+
+def grads_np(seed, n, scale, bf16, kind=S.KIND_NORMAL):
+    cache = {}
+
+    def grad_of(t, mb):
+        if (t, mb) not in cache:
+            g = S.fill(n, seed, S.TAG_GRAD, mb, t, scale, kind)
+            cache[(t, mb)] = S.bf16_bits_to_f32(S.f32_to_bf16_bits(g)) if bf16 else g
+        return cache[(t, mb)]
+    return grad_of
+
+
+def compare_iteration(o32, s, N, before):
+    """grad_out bit-exact; AdamW state against the fp64 step from the same gradient and state."""
+    g_gpu = s.grad_out[:N].cpu().numpy()
+    assert bits_equal(g_gpu, o32.grad_out), "iteration gradient differs from the fp32 oracle"
+    p, m, v = oracle_adamw.adamw_step(before[0], before[1], before[2], g_gpu, o32.t, **hp32())
+    assert max_rel(s.param[:N].cpu().numpy(), p) <= 1e-6
+    assert max_rel(s.exp_avg[:N].cpu().numpy(), m) <= 1e-6
+    assert max_rel(s.exp_avg_sq[:N].cpu().numpy(), v) <= 1e-6
+    # against the oracle's own running state (fp32 storage on both sides)
+    assert max_rel(s.param[:N].cpu().numpy(), o32.param) <= 1e-6
+    assert max_rel(s.exp_avg[:N].cpu().numpy(), o32.m) <= 1e-6
+    assert max_rel(s.exp_avg_sq[:N].cpu().numpy(), o32.v) <= 1e-6
+    torch = torch_()
+    pb = s.param_bf16[:N].view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(pb, S.f32_to_bf16_bits(s.param[:N].cpu().numpy()))
+
+
+def state_of(s, N):
+    return [x[:N].cpu().numpy().copy() for x in (s.param, s.exp_avg, s.exp_avg_sq)]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_ragged_shard_with_failures_matches_oracle(bf16):
+    """W=8, G=4 on a ragged tensor list: failure-free, two failures with partial in-place
+    synchronisation, promotion-free boundary, then steady state; every iteration compared."""
+    N = OFF[-1]
+    o32, s, eng = make_pair(8, 4, OFF, bf16, seed=3)
+    o64 = Proto(8, 4, OFF, dtype=np.float64)
+    o64.set_state(o32.param)
+    g = grads_np(3, N, 1e-3, bf16)
+    plan = [dict(), dict(dying={3: 2, 6: 2}, fidelity_k=4), dict(), dict(dying={0: 0}, snapshot_every=True), dict()]
+    for t, kw in enumerate(plan):
+        before = state_of(s, N)
+        a = run_iteration(o32, view_oracle, t, g, 8, hp=hp32(), **kw)
+        run_iteration(o64, view_oracle, t, g, 8, hp=hp32(), **kw)
+        b = run_iteration(eng, view_hip, t, g, 8, hp=hp32(), **kw)
+        assert a["ids"] == b["ids"]
+        for x, y in zip(a["decisions"], b["decisions"]):
+            for k in x:
+                assert x[k] == y[k], k
+        compare_iteration(o32, s, N, before)
+        assert max_rel(s.grad_out[:N].cpu().numpy(), o64.grad_out) <= 1e-6
+    if bf16:                                                   # against the unrounded samples
+        o_raw = Proto(8, 4, OFF, dtype=np.float64)
+        o_raw.set_state(o32.param)
+        g_raw = grads_np(3, N, 1e-3, False)
+        o_hip, s2, eng2 = make_pair(8, 4, OFF, True, seed=3)
+        run_iteration(o_raw, view_oracle, 0, g_raw, 8, hp=hp32())
+        run_iteration(eng2, view_hip, 0, g_raw, 8, hp=hp32())   # the adapter rounds to bf16 on upload
+        assert max_rel(s2.grad_out[:N].cpu().numpy(), o_raw.grad_out) <= 1e-2
+
+
+def test_tiny_config_full_comparison():
+    """Config 1: R=4, 1,048,576 elements, M=8, replica 2 fails after its first microbatch of
+    iteration 1, three iterations; the whole shard is compared."""
+    from tests.configs import CONFIGS
+    c = CONFIGS[1]
+    N = c["off"][-1]
+    o32, s, eng = make_pair(c["W"], c["G"], c["off"], False, seed=c["seed"])
+    g = grads_np(c["seed"], N, c["scale"], False)
+    for t in range(c["iters"]):
+        before = state_of(s, N)
+        kw = dict(dying=c["schedule"].get(t))
+        a = run_iteration(o32, view_oracle, t, g, c["W"], hp=hp32(), **kw)
+        b = run_iteration(eng, view_hip, t, g, c["W"], hp=hp32(), **kw)
+        assert a["ids"] == b["ids"]
+        if t == 1:
+            assert a["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
+        compare_iteration(o32, s, N, before)
+
+
+def test_failure_run_equals_clean_replay_bit_for_bit():
+    """Fixed-order mode: a run with failures, snapshots, in-place reductions and rewinds gives
+    the same bits (gradient and AdamW state) as a failure-free run that accumulates the same
+    ordered ids into the same replicas with the dead replicas absent from the start."""
+    torch = torch_()
+    N = OFF[-1]
+    _, s, eng = make_pair(8, 4, OFF, False, seed=5)
+    g = grads_np(5, N, 1e-3, False)
+    run_iteration(eng, view_hip, 0, g, 8, hp=hp32())
+    out = run_iteration(eng, view_hip, 1, g, 8, hp=hp32(), dying={3: 2, 6: 2}, fidelity_k=3, snapshot_every=True)
+    _, s2, eng2 = make_pair(8, 4, OFF, False, seed=5)
+    run_iteration(eng2, view_hip, 0, g, 8, hp=hp32())
+    # replay: feed exactly the audited ids; replicas 3 and 6 never accumulate
+    s2.on_failure([3, 6])
+    s2.restore()
+    for r, ids in out["ids"].items():
+        for mb in ids:
+            assert eng2.accumulate(r, mb, g(1, mb))
+    s2.reduce()
+    assert torch.equal(s.grad_out, s2.grad_out)
+    s2.adamw_step(**hp32())
+    s2.advance()
+    for x, y in [(s.param, s2.param), (s.exp_avg, s2.exp_avg), (s.exp_avg_sq, s2.exp_avg_sq)]:
+        assert torch.equal(x, y)
+
+
+def test_restore_equals_never_accumulated():
+    """Partial microbatch on the survivors at failure time, then rewind: buffers equal those of
+    a run that never started that microbatch (bit-exact copies)."""
+    torch = torch_()
+    N = OFF[-1]
+    g = grads_np(7, N, 1e-3, False)
+    runs = []
+    for partial in (True, False):
+        o, s, eng = make_pair(4, 2, OFF, False, seed=7)
+        for e, gg in ((o, g), (eng, g)):
+            for r in range(4):
+                e.accumulate(r, r, gg(0, r))
+            e.snapshot(None)
+            if partial:
+                for r in (0, 1, 3):
+                    e.accumulate(r, r + 4, gg(0, r + 4), 0, 6)
+            e.on_failure([2])
+            e.restore(None, stale_only=True)
+        for r in (0, 1, 3):
+            assert bits_equal(s.acc[r][:N].cpu().numpy(), o.acc[r])
+        assert view_hip(s)["contributed"] == list(o.world.contributed)
+        runs.append(s)
+    for r in (0, 1, 3):
+        assert torch.equal(runs[0].acc[r], runs[1].acc[r])
+
+
+def test_negative_zero_and_stale_buffers():
+    torch = torch_()
+    s = B.Shard(1, 2, [0, 7])
+    s.acc[0].fill_(123.0)
+    g0 = torch.tensor([-0.0, 1.0, -2.0, 0.0, -0.0, 5.0, -0.0, 0.0], device="cuda")
+    s.accumulate(0, 0, g0)
+    got = s.acc[0][:7].cpu().numpy()
+    assert np.array_equal(got, np.array([0, 1, -2, 0, 0, 5, 0], np.float32))
+    assert list(np.signbit(got)) == [False, False, True, False, False, False, False]   # (+0) + (-0) = +0
+
+
+def test_launch_shapes_do_not_change_the_bits():
+    torch = torch_()
+    N = OFF[-1]
+    g = grads_np(11, N, 1e-3, False)
+    ref = None
+    try:
+        for U in (1, 2, 4, 8):
+            for nt in (0, 1):
+                for cap in (0, 3):
+                    assert B.recover_set_tuning(0, U) == 0 and B.recover_set_tuning(1, nt) == 0
+                    assert B.recover_set_tuning(2, cap) == 0
+                    _, s, eng = make_pair(4, 2, OFF, False, seed=11)
+                    run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={1: 1}, fidelity_k=2)
+                    cur = [x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)]
+                    if ref is None:
+                        ref = cur
+                    for x, y in zip(ref, cur):
+                        assert torch.equal(x, y), (U, nt, cap)
+    finally:
+        B.recover_set_tuning(0, 4)
+        B.recover_set_tuning(1, 1)
+        B.recover_set_tuning(2, 0)
+
+
+def test_promoted_spare_and_inplace_sum_on_gpu():
+    """Six replicas, one lost (boundary), then a major lost while a major-spare exists: the
+    spare's buffer, overwritten by the in-place sum, is rewound and admitted."""
+    N = OFF[-1]
+    o32, s, eng = make_pair(6, 2, OFF, False, seed=13)
+    g = grads_np(13, N, 1e-3, False)
+    for t, kw in enumerate([dict(dying={5: 2}), dict(dying={1: 2}, fidelity_k=5), dict()]):
+        before = state_of(s, N)
+        a = run_iteration(o32, view_oracle, t, g, 6, hp=hp32(), **kw)
+        b = run_iteration(eng, view_hip, t, g, 6, hp=hp32(), **kw)
+        assert a["ids"] == b["ids"]
+        if t == 1:
+            assert not b["decisions"][0]["at_boundary"] and b["decisions"][0]["role"][4] == B.ROLE_MAJOR
+        compare_iteration(o32, s, N, before)
+
+
+def test_adaptive_policy_divides_by_the_committed_count():
+    N = OFF[-1]
+    o32, s, eng = make_pair(4, 2, OFF, False, seed=17, flags=B.FLAG_ADAPTIVE)
+    g = grads_np(17, N, 1e-3, False)
+    before = state_of(s, N)
+    a = run_iteration(o32, view_oracle, 0, g, 4, hp=hp32(), dying={2: 1})
+    b = run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={2: 1})
+    assert a["ids"] == b["ids"] and sum(len(v) for v in b["ids"].values()) == 6
+    compare_iteration(o32, s, N, before)
