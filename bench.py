@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the gradient path on one MI355X.
+
+A step is one failure-free iteration of the GPT-2-small-sized shard (8 replicas, 32
+microbatches, fp32 gradients, 148 tensors, 123,589,632 elements) through the C ABI:
+32 x recover_accumulate, recover_reduce, recover_adamw_step, recover_policy_adjust.
+Gradients are synthetic (seeded Philox streams), pre-generated into a pool of four HBM
+buffers before the timed region: generating them stands in for the backward pass.
+
+Prints ONE JSON line: effective HBM GB/s = algorithmic bytes per iteration / time, with a
+`roofline` object for the dominant kernel (the read-modify-write accumulate, timed with
+events on the launch stream inside the timed region) and a `cpu_baseline` object (the CPU
+oracle, as it stands, on a bounded slice of the same workload).  Extra keys report each
+kernel's rate and the same iteration with a snapshot of every replica, timed separately.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+POOL = 4
+
+
+def workload():
+    from paper_2605_11215_amd.workloads import CONFIGS
+    return CONFIGS[2]
+
+
+def bytes_per_elem(W, M, s_g, R_c):
+    """Algorithmic bytes per element of one failure-free iteration: first microbatch of a
+    replica writes acc and reads g; later ones also read acc; reduce reads R_c buffers and
+    writes one; AdamW reads g,p,m,v and writes p,m,v."""
+    acc = W * (s_g + 4) + (M - W) * (s_g + 8)
+    return dict(accumulate=acc, reduce=4 * R_c + 4, adamw=28, total=acc + 4 * R_c + 4 + 28)
+
+
+def read_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", "accumulate_f32_gpt2_shard_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(c, pool_slices, iters):
+    """The oracle's fp32 protocol simulator on a contiguous slice: `iters` failure-free
+    iterations (32 accumulates, reduce, AdamW).  Only this leg touches oracle/."""
+    import numpy as np
+    from oracle.proto import Proto
+    n = len(pool_slices[0])
+    W, G = c["W"], c["G"]
+    p = Proto(W, G, [0, n], dtype=np.float32)
+    p.set_state(np.zeros(n, np.float32))
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        for k in range(G):
+            for r in range(W):
+                p.accumulate(r, r + W * k, pool_slices[(k * W + r) % POOL])
+        p.reduce()
+        p.adamw_step(**HP)
+        p.advance()
+    dt = time.perf_counter() - t0
+    b = bytes_per_elem(W, W * G, 4, W)["total"]
+    return dict(value=b * n * iters / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
+                sample="%d failure-free iterations of the same workload on a contiguous slice of %d elements "
+                       "(oracle.proto.Proto, fp32, NumPy, one thread; %.1f s)" % (iters, n, dt),
+                seconds=dt, host_cpus=os.cpu_count())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-slice", type=int, default=1 << 24)
+    ap.add_argument("--cpu-iters", type=int, default=16)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's HBM); "
+              "--gpus %d is not supported" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_11215_amd import binding as B
+    from paper_2605_11215_amd import synth
+    from paper_2605_11215_amd.synth import reference_np as S
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; this library has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    B.lib()
+
+    c = workload()
+    W, G, off = c["W"], c["G"], c["off"]
+    N, M = off[-1], c["W"] * c["G"]
+    T = len(off) - 1
+    torch.cuda.set_device(0)
+    sh = B.Shard(W, G, off, device="cuda:0", snapshots=True)
+    synth.fill_device(sh.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=N)
+    pool = [synth.fill_device(torch.empty(N, dtype=torch.float32, device="cuda:0"), c["seed"], S.TAG_GRAD, j, 0,
+                              c["scale"]) for j in range(POOL)]
+    gptr = [g.data_ptr() for g in pool]
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = sh.ctx
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def iteration(marks=None, snapshot=False):
+        """One failure-free iteration.  marks: list receiving event pairs per phase."""
+        e = [ev() for _ in range(5)] if marks is not None else None
+        if e:
+            e[0].record()
+        for r in range(W):                                    # k = 0: overwrite variant
+            rc = B.recover_accumulate(ctx, r, r, gptr[r % POOL], B.F32, 0, T, stream)
+            assert rc == 0, rc
+        if e:
+            e[1].record()
+        for k in range(1, G):                                 # read-modify-write variant
+            for r in range(W):
+                rc = B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], B.F32, 0, T, stream)
+                assert rc == 0, rc
+        if e:
+            e[2].record()
+        if snapshot:
+            assert B.recover_snapshot(ctx, -1, 0, T, stream) == 0
+        assert B.recover_reduce(ctx, 0, T, 0, stream) == 0
+        if e:
+            e[3].record()
+        assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], stream) == 0
+        if e:
+            e[4].record()
+            marks.append(e)
+        rc, _ = B.recover_policy_adjust(ctx, [], W)
+        assert rc == 0
+
+    for _ in range(a.warmup):
+        iteration()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        iteration(marks)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt * 1e3 / a.steps
+
+    bpe = bytes_per_elem(W, M, 4, W)
+    gbs = bpe["total"] * N / (dt / a.steps) / 1e9
+    phase = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]     # ms per iteration
+    n_rmw = (G - 1) * W
+    rmw_ms = phase[1] / n_rmw
+    k_gbs = dict(accumulate_first=W * 8 * N / phase[0] / 1e6, accumulate_rmw=12 * N / rmw_ms / 1e6,
+                 reduce=bpe["reduce"] * N / phase[2] / 1e6, adamw=28 * N / phase[3] / 1e6)
+
+    # the same iteration with a snapshot of every replica before the reduction (Alg. 1 lines 9-10)
+    for _ in range(2):
+        iteration(snapshot=True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ns = max(5, a.steps // 5)
+    for _ in range(ns):
+        iteration(snapshot=True)
+    torch.cuda.synchronize()
+    dts = (time.perf_counter() - t1) / ns
+    with_snapshot = dict(ms_per_step=dts * 1e3, bytes_per_elem=bpe["total"] + 8 * W,
+                         GBps=(bpe["total"] + 8 * W) * N / dts / 1e9)
+
+    out = {
+        "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[1] GPT-2-small-sized shard: 123,589,632 fp32 elements in 148 tensors, "
+                               "R=8 replicas, M=32 microbatches/iteration, failure-free iteration",
+                   "replicas": W, "microbatches": M, "n_elems": N, "n_tensors": T,
+                   "bytes_per_elem": bpe["total"], "grad_pool_buffers": POOL},
+        "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "microbatches_per_s": M / (dt / a.steps),
+        "kernel_GBps": k_gbs,
+        "phase_ms": dict(accumulate_first=phase[0], accumulate_rmw=phase[1], reduce=phase[2], adamw=phase[3]),
+        "with_snapshot": with_snapshot,
+        "roofline": {"bound": "hbm", "kernel": "k_accumulate<float, RMW>", "achieved": k_gbs["accumulate_rmw"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
+                     "traffic": read_traffic(), "bytes_per_launch": 12 * N, "avg_launch_ms": rmw_ms,
+                     "launches_timed": n_rmw * len(marks)},
+    }
+    if not a.no_cpu_baseline:
+        n = min(a.cpu_slice, N)
+        slices = [g[:n].cpu().numpy() for g in pool]
+        out["cpu_baseline"] = cpu_baseline(c, slices, a.cpu_iters)
+    sh.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
