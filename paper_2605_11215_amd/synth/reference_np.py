@@ -120,9 +120,11 @@ def values(idx, seed, tag, mb_id, it, scale, kind=KIND_NORMAL):
     idx = np.asarray(idx, np.uint64)
     if kind == KIND_NORMAL:
         x = philox4x32_10(idx >> np.uint64(2), mb_id, it, KIND_NORMAL, seed, tag)
-        z = _four_normals(*x)
         lane = (idx & np.uint64(3)).astype(np.int64)
-        zz = np.where(lane == 0, z[0], np.where(lane == 1, z[1], np.where(lane == 2, z[2], z[3])))
+        second = lane >= 2                                  # lanes 2, 3 come from words 2, 3
+        r = np.sqrt(-2.0 * _ln_u(_numerator(np.where(second, x[2], x[0]))))
+        c, s = _cos_sin_2pi_u(_numerator(np.where(second, x[3], x[1])))
+        zz = r * np.where((lane & 1) == 0, c, s)
         return (float(scale) * zz).astype(np.float32)
     if kind == KIND_STUDENT_T3:
         x = philox4x32_10(idx, mb_id, it, KIND_STUDENT_T3, seed, tag)
