@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-slice", type=int, default=1 << 24)
     ap.add_argument("--cpu-iters", type=int, default=16)
+    ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's HBM); "
@@ -99,6 +100,9 @@ def main():
         print("bench.py: no GPU visible; this library has no CPU path", file=sys.stderr)
         sys.exit(3)
     B.lib()
+    for kv in filter(None, a.tuning.split(",")):
+        k, v = kv.split("=")
+        assert B.recover_set_tuning(int(k), int(v)) == 0, kv
 
     c = workload()
     W, G, off = c["W"], c["G"], c["off"]

@@ -82,11 +82,16 @@ __device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to
 // ---------------------------------------------------------------------------------------------
 template <typename G, int U, bool NT, bool FIRST>
 __global__ __launch_bounds__(kThreads) void k_accumulate(float *__restrict__ acc, const G *__restrict__ g,
-                                                         Span sp, size_t ntiles) {
+                                                         Span sp, size_t ntiles, int xcd_chunked) {
   f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
   const G *gv = g + sp.vbegin;
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  size_t first = blockIdx.x, stride = gridDim.x;
+  if (xcd_chunked) {  // grid = 8 * ceil(ntiles / 8): one tile per workgroup, XCD x owns the x-th eighth
+    first = size_t(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    stride = ntiles;
+  }
+  for (size_t tile = first; tile < ntiles; tile += stride) {
     const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
     f32x4 x[U], a[U];
     if (base + size_t(kThreads) * (U - 1) < sp.nvec) {
@@ -148,45 +153,68 @@ __global__ __launch_bounds__(kThreads) void k_copy(float *__restrict__ dst, cons
 
 // ---------------------------------------------------------------------------------------------
 // reduce: out[i] = ((src0[i] + src1[i]) + ...) / divisor, ascending contributor order; in-place mode
-// also stores the undivided sum to every sum_dst buffer.  Contributor loads are issued eight at a
-// time; the adds stay strictly left to right.
+// also stores the undivided sum to every sum_dst buffer.  A workgroup walks the contributors one
+// after the other over its whole tile (U consecutive 4 KiB rows per contributor), two contributors'
+// loads in flight at a time, so each of its bursts reads one buffer contiguously; every element's
+// adds stay strictly left to right.
 // ---------------------------------------------------------------------------------------------
-constexpr int kReduceBatch = 8;
-
-template <bool NT>
-__device__ inline f32x4 reduce_vec(const ReduceArgs &a, size_t vec_index, size_t vbegin) {
-  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-  for (int r0 = 0; r0 < a.n_src; r0 += kReduceBatch) {
-    f32x4 t[kReduceBatch];
-#pragma unroll
-    for (int j = 0; j < kReduceBatch; ++j)
-      if (r0 + j < a.n_src) t[j] = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r0 + j] + vbegin) + vec_index);
-#pragma unroll
-    for (int j = 0; j < kReduceBatch; ++j)
-      if (r0 + j < a.n_src) sum = (r0 + j == 0) ? t[j] : sum + t[j];
-  }
-  return sum;
-}
-
 template <int U, bool NT, bool INPLACE>
 __global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size_t ntiles) {
   f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) ok[u] = base + size_t(kThreads) * u < sp.nvec;
+    f32x4 sum[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) sum[u] = zero;
+    int r = 0;
+    if (a.n_src > 0) {
+      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + base;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) sum[u] = ld<NT>(s0 + size_t(kThreads) * u);
+      r = 1;
+    }
+    for (; r + 1 < a.n_src; r += 2) {
+      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
+      const f32x4 *s1 = reinterpret_cast<const f32x4 *>(a.src[r + 1] + sp.vbegin) + base;
+      f32x4 t0[U], t1[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) t0[u] = ld<NT>(s0 + size_t(kThreads) * u);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) t1[u] = ld<NT>(s1 + size_t(kThreads) * u);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) sum[u] = (sum[u] + t0[u]) + t1[u];
+    }
+    if (r < a.n_src) {
+      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) sum[u] = sum[u] + ld<NT>(s0 + size_t(kThreads) * u);
+    }
+    if (INPLACE) {
+      for (int d = 0; d < a.n_sum_dst; ++d) {
+        f32x4 *dd = reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + base;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (ok[u]) st<NT>(dd + size_t(kThreads) * u, sum[u]);
+      }
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t i = base + size_t(kThreads) * u;
-      if (i < sp.nvec) {
-        f32x4 sum = reduce_vec<NT>(a, i, sp.vbegin);
-        if (INPLACE) {
-          for (int d = 0; d < a.n_sum_dst; ++d) st<NT>(reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + i, sum);
-        }
+      if (ok[u]) {
         f32x4 q;
-        q.x = sum.x / a.divisor;
-        q.y = sum.y / a.divisor;
-        q.z = sum.z / a.divisor;
-        q.w = sum.w / a.divisor;
-        st<NT>(o4 + i, q);
+        q.x = sum[u].x / a.divisor;
+        q.y = sum[u].y / a.divisor;
+        q.z = sum[u].z / a.divisor;
+        q.w = sum[u].w / a.divisor;
+        st<NT>(o4 + base + size_t(kThreads) * u, q);
       }
     }
   }
@@ -326,21 +354,23 @@ hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bo
   unsigned grid;
   size_t ntiles;
   if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  const int xc = tuning().xcd_chunked && tuning().grid_cap == 0 && ntiles >= 64 ? 1 : 0;
+  if (xc) grid = (unsigned)(((ntiles + 7) / 8) * 8);
   if (grad_is_bf16) {
     const uint16_t *g = static_cast<const uint16_t *>(grad);
     RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
       if (first)
-        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
       else
-        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
     });
   } else {
     const float *g = static_cast<const float *>(grad);
     RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
       if (first)
-        hipLaunchKernelGGL((k_accumulate<float, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+        hipLaunchKernelGGL((k_accumulate<float, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
       else
-        hipLaunchKernelGGL((k_accumulate<float, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles);
+        hipLaunchKernelGGL((k_accumulate<float, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
     });
   }
   return hipGetLastError();
@@ -349,7 +379,7 @@ hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bo
 hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   Span sp = make_span(begin, end);
-  const int Uv = tuning().vecs_per_thread;
+  const int Uv = tuning().copy_vecs;
   unsigned grid;
   size_t ntiles;
   if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
@@ -362,17 +392,16 @@ hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, h
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   Span sp = make_span(begin, end);
-  int Uv = tuning().vecs_per_thread > 2 ? 2 : tuning().vecs_per_thread;
+  const int Uv = tuning().reduce_vecs;
   unsigned grid;
   size_t ntiles;
   if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
   const bool inplace = a.n_sum_dst > 0;
   RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
-    constexpr int UR = U > 2 ? 2 : U;
     if (inplace)
-      hipLaunchKernelGGL((k_reduce<UR, NT, true>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
+      hipLaunchKernelGGL((k_reduce<U, NT, true>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
     else
-      hipLaunchKernelGGL((k_reduce<UR, NT, false>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
+      hipLaunchKernelGGL((k_reduce<U, NT, false>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
   });
   return hipGetLastError();
 }
@@ -382,16 +411,15 @@ hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *
                         float inv_sqrt_bc2, float eps, hipStream_t s) {
   if (n == 0) return hipSuccess;
   AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
-  int Uv = tuning().vecs_per_thread > 2 ? 2 : tuning().vecs_per_thread;
+  const int Uv = tuning().adamw_vecs;
   unsigned grid;
   size_t ntiles;
   if (!grid_for(n / 4, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
   RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
-    constexpr int UA = U > 2 ? 2 : U;
     if (p_bf16)
-      hipLaunchKernelGGL((k_adamw<UA, NT, true>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+      hipLaunchKernelGGL((k_adamw<U, NT, true>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
     else
-      hipLaunchKernelGGL((k_adamw<UA, NT, false>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+      hipLaunchKernelGGL((k_adamw<U, NT, false>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
   });
   return hipGetLastError();
 }

@@ -604,6 +604,16 @@ int recover_set_tuning(int key, int value) {
       if (value < 0 || value > (1 << 24)) return RECOVER_ERR_ARG;
       t.grid_cap = value;
       return RECOVER_OK;
+    case 6:
+      if (value != 0 && value != 1) return RECOVER_ERR_ARG;
+      t.xcd_chunked = value;
+      return RECOVER_OK;
+    case 3:
+    case 4:
+    case 5:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return RECOVER_ERR_ARG;
+      (key == 3 ? t.reduce_vecs : key == 4 ? t.adamw_vecs : t.copy_vecs) = value;
+      return RECOVER_OK;
   }
   return RECOVER_ERR_ARG;
 }

@@ -212,21 +212,19 @@ def test_launch_shapes_do_not_change_the_bits():
     ref = None
     try:
         for U in (1, 2, 4, 8):
-            for nt in (0, 1):
-                for cap in (0, 3):
-                    assert B.recover_set_tuning(0, U) == 0 and B.recover_set_tuning(1, nt) == 0
-                    assert B.recover_set_tuning(2, cap) == 0
-                    _, s, eng = make_pair(4, 2, OFF, False, seed=11)
-                    run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={1: 1}, fidelity_k=2)
-                    cur = [x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)]
-                    if ref is None:
-                        ref = cur
-                    for x, y in zip(ref, cur):
-                        assert torch.equal(x, y), (U, nt, cap)
+            for nt, cap, xcd in ((1, 0, 1), (0, 0, 0), (1, 3, 0), (0, 2, 1)):
+                for key, val in ((0, U), (3, U), (4, U), (5, U), (1, nt), (2, cap), (6, xcd)):
+                    assert B.recover_set_tuning(key, val) == 0
+                _, s, eng = make_pair(4, 2, OFF, False, seed=11)
+                run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={1: 1}, fidelity_k=2)
+                cur = [x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)]
+                if ref is None:
+                    ref = cur
+                for x, y in zip(ref, cur):
+                    assert torch.equal(x, y), (U, nt, cap, xcd)
     finally:
-        B.recover_set_tuning(0, 4)
-        B.recover_set_tuning(1, 1)
-        B.recover_set_tuning(2, 0)
+        for key, val in ((0, 1), (1, 1), (2, 0), (3, 1), (4, 4), (5, 1), (6, 1)):      # the defaults
+            B.recover_set_tuning(key, val)
 
 
 def test_promoted_spare_and_inplace_sum_on_gpu():
