@@ -180,9 +180,10 @@ int recover_committed_ids(recover_ctx *ctx, int replica, uint32_t *ids_out, int 
 const char *recover_last_error(const recover_ctx *ctx);
 
 /* Launch-shape knobs for measurement sweeps (process-wide; values outside the documented sets are
- * rejected with ERR_ARG).  key 0: accumulate vectors per thread {1,2,4,8}; key 1: nontemporal loads/stores
- * {0,1}; key 2: grid cap in workgroups, 0 = one tile per workgroup; keys 3, 4, 5: vectors per thread of the
- * reduce, AdamW and copy kernels {1,2,4,8}.  The results do not depend on any of them. */
+ * rejected with ERR_ARG).  key 0: accumulate vectors per lane {1,2,4}; key 1: nontemporal loads/stores
+ * {0,1}; key 2: grid cap in workgroups, 0 = one tile per workgroup; keys 3, 4, 5: vectors per lane of the
+ * reduce, AdamW and copy kernels {1,2,4}; key 6: XCD-chunked tile order of accumulate {0,1}; key 7: lanes
+ * per workgroup {64,256}.  The results do not depend on any of them. */
 int recover_set_tuning(int key, int value);
 
 #ifdef __cplusplus

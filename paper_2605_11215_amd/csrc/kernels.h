@@ -10,13 +10,14 @@ namespace recover {
 constexpr int kMaxReplicas = 64;
 
 struct Tuning {
+  int threads = 64;         // lanes per workgroup: 64 (one wavefront) or 256
   int vecs_per_thread = 1;  // accumulate: 128-bit vectors each lane keeps in flight per stream
   int nontemporal = 1;      // streaming cache hints on loads and stores
   int grid_cap = 0;         // 0: one tile per workgroup; else grid-stride over at most this many
   int reduce_vecs = 1;      // reduce: vectors per lane (each with up to 8 contributor loads in flight)
-  int adamw_vecs = 4;       // AdamW: vectors per lane (four loads each)
+  int adamw_vecs = 1;       // AdamW: vectors per lane (four loads each)
   int copy_vecs = 1;        // snapshot / restore copy: vectors per lane
-  int xcd_chunked = 1;      // accumulate: 1 = workgroup b works in the b%8-th eighth of the range (one
+  int xcd_chunked = 0;      // accumulate: 1 = workgroup b works in the b%8-th eighth of the range (one
                             // contiguous region per XCD) instead of tile b
 };
 Tuning &tuning();

@@ -1,18 +1,20 @@
 // gfx950 kernels of the gradient path.  Every step is an elementwise stream over flat fp32
 // buffers, bound by HBM bandwidth, so the design is the same everywhere: one 128-bit load or
 // store per lane per access (a wavefront moves 1 KiB of consecutive bytes per instruction),
-// several independent vectors in flight per lane before the first use, 64-bit element indices
-// (a shard can exceed 2^32 bytes), no LDS (no element is used twice) and no atomics (the sums
-// have a fixed order).  Ranges that do not start or end on a 16-byte boundary get their ragged
-// ends from a few lanes of workgroup 0.
+// one-wavefront workgroups with one tile each (a finished wavefront frees its slot at once; measured
+// 4 % faster than four-wavefront groups), U independent vectors in flight per lane before the first
+// use, 64-bit element indices (a shard can exceed 2^32 bytes), no LDS (no element is used twice) and
+// no atomics (the sums have a fixed order).  Ranges that do not start or end on a 16-byte boundary
+// get their ragged ends from a few lanes of workgroup 0.
 #include "kernels.h"
+
+#include <type_traits>
 
 namespace recover {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
 
 Tuning &tuning() {
   static Tuning t;
@@ -80,8 +82,8 @@ __device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to
 // ---------------------------------------------------------------------------------------------
 // accumulate: acc[i] = acc[i] + widen(g[i]);  FIRST: acc[i] = (+0) + widen(g[i])
 // ---------------------------------------------------------------------------------------------
-template <typename G, int U, bool NT, bool FIRST>
-__global__ __launch_bounds__(kThreads) void k_accumulate(float *__restrict__ acc, const G *__restrict__ g,
+template <typename G, int T, int U, bool NT, bool FIRST>
+__global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, const G *__restrict__ g,
                                                          Span sp, size_t ntiles, int xcd_chunked) {
   f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
   const G *gv = g + sp.vbegin;
@@ -92,21 +94,21 @@ __global__ __launch_bounds__(kThreads) void k_accumulate(float *__restrict__ acc
     stride = ntiles;
   }
   for (size_t tile = first; tile < ntiles; tile += stride) {
-    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    const size_t base = tile * size_t(T * U) + threadIdx.x;
     f32x4 x[U], a[U];
-    if (base + size_t(kThreads) * (U - 1) < sp.nvec) {
+    if (base + size_t(T) * (U - 1) < sp.nvec) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) x[u] = load_grad<NT>(gv, base + size_t(kThreads) * u);
+      for (int u = 0; u < U; ++u) x[u] = load_grad<NT>(gv, base + size_t(T) * u);
       if (!FIRST) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld<NT>(a4 + base + size_t(kThreads) * u);
+        for (int u = 0; u < U; ++u) a[u] = ld<NT>(a4 + base + size_t(T) * u);
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) st<NT>(a4 + base + size_t(kThreads) * u, (FIRST ? zero : a[u]) + x[u]);
+      for (int u = 0; u < U; ++u) st<NT>(a4 + base + size_t(T) * u, (FIRST ? zero : a[u]) + x[u]);
     } else {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const size_t i = base + size_t(kThreads) * u;
+        const size_t i = base + size_t(T) * u;
         if (i < sp.nvec) {
           f32x4 xv = load_grad<NT>(gv, i);
           f32x4 av = FIRST ? zero : ld<NT>(a4 + i);
@@ -124,23 +126,23 @@ __global__ __launch_bounds__(kThreads) void k_accumulate(float *__restrict__ acc
 // ---------------------------------------------------------------------------------------------
 // copy (snapshot and restore): dst[i] = src[i]
 // ---------------------------------------------------------------------------------------------
-template <int U, bool NT>
-__global__ __launch_bounds__(kThreads) void k_copy(float *__restrict__ dst, const float *__restrict__ src, Span sp,
+template <int T, int U, bool NT>
+__global__ __launch_bounds__(T) void k_copy(float *__restrict__ dst, const float *__restrict__ src, Span sp,
                                                    size_t ntiles) {
   f32x4 *d4 = reinterpret_cast<f32x4 *>(dst + sp.vbegin);
   const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + sp.vbegin);
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    const size_t base = tile * size_t(T * U) + threadIdx.x;
     f32x4 x[U];
-    if (base + size_t(kThreads) * (U - 1) < sp.nvec) {
+    if (base + size_t(T) * (U - 1) < sp.nvec) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) x[u] = ld<NT>(s4 + base + size_t(kThreads) * u);
+      for (int u = 0; u < U; ++u) x[u] = ld<NT>(s4 + base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u) st<NT>(d4 + base + size_t(kThreads) * u, x[u]);
+      for (int u = 0; u < U; ++u) st<NT>(d4 + base + size_t(T) * u, x[u]);
     } else {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const size_t i = base + size_t(kThreads) * u;
+        const size_t i = base + size_t(T) * u;
         if (i < sp.nvec) st<NT>(d4 + i, ld<NT>(s4 + i));
       }
     }
@@ -158,15 +160,15 @@ __global__ __launch_bounds__(kThreads) void k_copy(float *__restrict__ dst, cons
 // loads in flight at a time, so each of its bursts reads one buffer contiguously; every element's
 // adds stay strictly left to right.
 // ---------------------------------------------------------------------------------------------
-template <int U, bool NT, bool INPLACE>
-__global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size_t ntiles) {
+template <int T, int U, bool NT, bool INPLACE>
+__global__ __launch_bounds__(T) void k_reduce(ReduceArgs a, Span sp, size_t ntiles) {
   f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    const size_t base = tile * size_t(T * U) + threadIdx.x;
     bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = base + size_t(kThreads) * u < sp.nvec;
+    for (int u = 0; u < U; ++u) ok[u] = base + size_t(T) * u < sp.nvec;
     f32x4 sum[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) sum[u] = zero;
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size
       const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + base;
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (ok[u]) sum[u] = ld<NT>(s0 + size_t(kThreads) * u);
+        if (ok[u]) sum[u] = ld<NT>(s0 + size_t(T) * u);
       r = 1;
     }
     for (; r + 1 < a.n_src; r += 2) {
@@ -184,10 +186,10 @@ __global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size
       f32x4 t0[U], t1[U];
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (ok[u]) t0[u] = ld<NT>(s0 + size_t(kThreads) * u);
+        if (ok[u]) t0[u] = ld<NT>(s0 + size_t(T) * u);
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (ok[u]) t1[u] = ld<NT>(s1 + size_t(kThreads) * u);
+        if (ok[u]) t1[u] = ld<NT>(s1 + size_t(T) * u);
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (ok[u]) sum[u] = (sum[u] + t0[u]) + t1[u];
@@ -196,14 +198,14 @@ __global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size
       const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (ok[u]) sum[u] = sum[u] + ld<NT>(s0 + size_t(kThreads) * u);
+        if (ok[u]) sum[u] = sum[u] + ld<NT>(s0 + size_t(T) * u);
     }
     if (INPLACE) {
       for (int d = 0; d < a.n_sum_dst; ++d) {
         f32x4 *dd = reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + base;
 #pragma unroll
         for (int u = 0; u < U; ++u)
-          if (ok[u]) st<NT>(dd + size_t(kThreads) * u, sum[u]);
+          if (ok[u]) st<NT>(dd + size_t(T) * u, sum[u]);
       }
     }
 #pragma unroll
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce(ReduceArgs a, Span sp, size
         q.y = sum[u].y / a.divisor;
         q.z = sum[u].z / a.divisor;
         q.w = sum[u].w / a.divisor;
-        st<NT>(o4 + base + size_t(kThreads) * u, q);
+        st<NT>(o4 + base + size_t(T) * u, q);
       }
     }
   }
@@ -253,8 +255,8 @@ __device__ inline uint32_t f32_to_bf16_rne(float x) {
   return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
 
-template <int U, bool NT, bool BF16OUT>
-__global__ __launch_bounds__(kThreads) void k_adamw(float *__restrict__ p, float *__restrict__ m,
+template <int T, int U, bool NT, bool BF16OUT>
+__global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__restrict__ m,
                                                     float *__restrict__ v, const float *__restrict__ g,
                                                     uint16_t *__restrict__ pb, size_t n, AdamArgs h, size_t ntiles) {
   const size_t nvec = n / 4;
@@ -262,40 +264,52 @@ __global__ __launch_bounds__(kThreads) void k_adamw(float *__restrict__ p, float
   const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
   u32x2 *b2 = reinterpret_cast<u32x2 *>(pb);
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(kThreads * U) + threadIdx.x;
+    const size_t base = tile * size_t(T * U) + threadIdx.x;
     f32x4 gv[U], pv[U], mv[U], vv[U];
     bool ok[U];
 #pragma unroll
+    for (int u = 0; u < U; ++u) ok[u] = base + size_t(T) * u < nvec;
+    // one buffer after the other, U consecutive rows each
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) gv[u] = ld<NT>(g4 + base + size_t(T) * u);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) pv[u] = ld<NT>(p4 + base + size_t(T) * u);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) mv[u] = ld<NT>(m4 + base + size_t(T) * u);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) vv[u] = ld<NT>(v4 + base + size_t(T) * u);
+#pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t i = base + size_t(kThreads) * u;
-      ok[u] = i < nvec;
-      if (ok[u]) {
-        gv[u] = ld<NT>(g4 + i);
-        pv[u] = ld<NT>(p4 + i);
-        mv[u] = ld<NT>(m4 + i);
-        vv[u] = ld<NT>(v4 + i);
+#pragma unroll
+      for (int l = 0; l < 4; ++l) {
+        float pp = pv[u][l], mm = mv[u][l], v1 = vv[u][l];
+        adam1(pp, mm, v1, gv[u][l], h);
+        pv[u][l] = pp;
+        mv[u][l] = mm;
+        vv[u][l] = v1;
       }
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const size_t i = base + size_t(kThreads) * u;
-      if (ok[u]) {
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) st<NT>(p4 + base + size_t(T) * u, pv[u]);
 #pragma unroll
-        for (int l = 0; l < 4; ++l) {
-          float pp = pv[u][l], mm = mv[u][l], v1 = vv[u][l];
-          adam1(pp, mm, v1, gv[u][l], h);
-          pv[u][l] = pp;
-          mv[u][l] = mm;
-          vv[u][l] = v1;
-        }
-        st<NT>(p4 + i, pv[u]);
-        st<NT>(m4 + i, mv[u]);
-        st<NT>(v4 + i, vv[u]);
-        if (BF16OUT) {
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) st<NT>(m4 + base + size_t(T) * u, mv[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) st<NT>(v4 + base + size_t(T) * u, vv[u]);
+    if (BF16OUT) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (ok[u]) {
           u32x2 w;
           w.x = f32_to_bf16_rne(pv[u].x) | (f32_to_bf16_rne(pv[u].y) << 16);
           w.y = f32_to_bf16_rne(pv[u].z) | (f32_to_bf16_rne(pv[u].w) << 16);
-          st<NT>(b2 + i, w);
+          st<NT>(b2 + base + size_t(T) * u, w);
         }
       }
     }
@@ -316,8 +330,8 @@ __global__ __launch_bounds__(kThreads) void k_adamw(float *__restrict__ p, float
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-static bool grid_for(size_t nvec, int U, unsigned *grid, size_t *ntiles) {
-  size_t tiles = (nvec + size_t(kThreads) * U - 1) / (size_t(kThreads) * U);
+static bool grid_for(size_t nvec, int T, int U, unsigned *grid, size_t *ntiles) {
+  size_t tiles = (nvec + size_t(T) * U - 1) / (size_t(T) * U);
   *ntiles = tiles;
   size_t g = tiles ? tiles : 1;
   int cap = tuning().grid_cap;
@@ -327,81 +341,91 @@ static bool grid_for(size_t nvec, int U, unsigned *grid, size_t *ntiles) {
   return true;
 }
 
-#define RECOVER_DISPATCH_U_NT(U_, NT_, CALL)                    \
-  do {                                                          \
-    if (NT_) {                                                  \
-      switch (U_) {                                             \
-        case 1: { constexpr int U = 1; constexpr bool NT = true; CALL; } break;  \
-        case 2: { constexpr int U = 2; constexpr bool NT = true; CALL; } break;  \
-        case 8: { constexpr int U = 8; constexpr bool NT = true; CALL; } break;  \
-        default: { constexpr int U = 4; constexpr bool NT = true; CALL; } break; \
-      }                                                         \
-    } else {                                                    \
-      switch (U_) {                                             \
-        case 1: { constexpr int U = 1; constexpr bool NT = false; CALL; } break;  \
-        case 2: { constexpr int U = 2; constexpr bool NT = false; CALL; } break;  \
-        case 8: { constexpr int U = 8; constexpr bool NT = false; CALL; } break;  \
-        default: { constexpr int U = 4; constexpr bool NT = false; CALL; } break; \
-      }                                                         \
-    }                                                           \
-  } while (0)
+template <int V>
+using Int = std::integral_constant<int, V>;
+
+// Calls f(Int<T>, Int<U>, bool_constant<NT>) for the run-time launch shape.
+template <typename F>
+static void with_shape(int T, int U, bool NT, F &&f) {
+  auto with_u = [&](auto t, auto nt) {
+    switch (U) {
+      case 2: f(t, Int<2>{}, nt); break;
+      case 4: f(t, Int<4>{}, nt); break;
+      default: f(t, Int<1>{}, nt); break;
+    }
+  };
+  auto with_nt = [&](auto t) {
+    if (NT)
+      with_u(t, std::true_type{});
+    else
+      with_u(t, std::false_type{});
+  };
+  if (T == 256)
+    with_nt(Int<256>{});
+  else
+    with_nt(Int<64>{});
+}
 
 hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bool first, size_t begin, size_t end,
                              hipStream_t s) {
   if (begin >= end) return hipSuccess;
-  Span sp = make_span(begin, end);
-  const int Uv = tuning().vecs_per_thread;
+  const Span sp = make_span(begin, end);
+  const int Uv = tuning().vecs_per_thread, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
-  if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
   const int xc = tuning().xcd_chunked && tuning().grid_cap == 0 && ntiles >= 64 ? 1 : 0;
   if (xc) grid = (unsigned)(((ntiles + 7) / 8) * 8);
-  if (grad_is_bf16) {
-    const uint16_t *g = static_cast<const uint16_t *>(grad);
-    RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+    constexpr int T = decltype(t)::value, U = decltype(u)::value;
+    constexpr bool NT = decltype(nt)::value;
+    if (grad_is_bf16) {
+      const uint16_t *g = static_cast<const uint16_t *>(grad);
       if (first)
-        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
+        hipLaunchKernelGGL((k_accumulate<uint16_t, T, U, NT, true>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
       else
-        hipLaunchKernelGGL((k_accumulate<uint16_t, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
-    });
-  } else {
-    const float *g = static_cast<const float *>(grad);
-    RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+        hipLaunchKernelGGL((k_accumulate<uint16_t, T, U, NT, false>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
+    } else {
+      const float *g = static_cast<const float *>(grad);
       if (first)
-        hipLaunchKernelGGL((k_accumulate<float, U, NT, true>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
+        hipLaunchKernelGGL((k_accumulate<float, T, U, NT, true>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
       else
-        hipLaunchKernelGGL((k_accumulate<float, U, NT, false>), dim3(grid), dim3(kThreads), 0, s, acc, g, sp, ntiles, xc);
-    });
-  }
+        hipLaunchKernelGGL((k_accumulate<float, T, U, NT, false>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
+    }
+  });
   return hipGetLastError();
 }
 
 hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
-  Span sp = make_span(begin, end);
-  const int Uv = tuning().copy_vecs;
+  const Span sp = make_span(begin, end);
+  const int Uv = tuning().copy_vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
-  if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
-  RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
-    hipLaunchKernelGGL((k_copy<U, NT>), dim3(grid), dim3(kThreads), 0, s, dst, src, sp, ntiles);
+  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+    constexpr int T = decltype(t)::value, U = decltype(u)::value;
+    constexpr bool NT = decltype(nt)::value;
+    hipLaunchKernelGGL((k_copy<T, U, NT>), dim3(grid), dim3(T), 0, s, dst, src, sp, ntiles);
   });
   return hipGetLastError();
 }
 
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
-  Span sp = make_span(begin, end);
-  const int Uv = tuning().reduce_vecs;
+  const Span sp = make_span(begin, end);
+  const int Uv = tuning().reduce_vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
-  if (!grid_for(sp.nvec, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
   const bool inplace = a.n_sum_dst > 0;
-  RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+    constexpr int T = decltype(t)::value, U = decltype(u)::value;
+    constexpr bool NT = decltype(nt)::value;
     if (inplace)
-      hipLaunchKernelGGL((k_reduce<U, NT, true>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
+      hipLaunchKernelGGL((k_reduce<T, U, NT, true>), dim3(grid), dim3(T), 0, s, a, sp, ntiles);
     else
-      hipLaunchKernelGGL((k_reduce<U, NT, false>), dim3(grid), dim3(kThreads), 0, s, a, sp, ntiles);
+      hipLaunchKernelGGL((k_reduce<T, U, NT, false>), dim3(grid), dim3(T), 0, s, a, sp, ntiles);
   });
   return hipGetLastError();
 }
@@ -410,16 +434,18 @@ hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *
                         float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float step_size,
                         float inv_sqrt_bc2, float eps, hipStream_t s) {
   if (n == 0) return hipSuccess;
-  AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
-  const int Uv = tuning().adamw_vecs;
+  const AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
+  const int Uv = tuning().adamw_vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
-  if (!grid_for(n / 4, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
-  RECOVER_DISPATCH_U_NT(Uv, tuning().nontemporal, {
+  if (!grid_for(n / 4, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+    constexpr int T = decltype(t)::value, U = decltype(u)::value;
+    constexpr bool NT = decltype(nt)::value;
     if (p_bf16)
-      hipLaunchKernelGGL((k_adamw<U, NT, true>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+      hipLaunchKernelGGL((k_adamw<T, U, NT, true>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
     else
-      hipLaunchKernelGGL((k_adamw<U, NT, false>), dim3(grid), dim3(kThreads), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+      hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
   });
   return hipGetLastError();
 }

@@ -592,8 +592,12 @@ int recover_committed_ids(recover_ctx *c, int r, uint32_t *ids_out, int cap) {
 int recover_set_tuning(int key, int value) {
   recover::Tuning &t = recover::tuning();
   switch (key) {
+    case 7:
+      if (value != 64 && value != 256) return RECOVER_ERR_ARG;
+      t.threads = value;
+      return RECOVER_OK;
     case 0:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return RECOVER_ERR_ARG;
+      if (value != 1 && value != 2 && value != 4) return RECOVER_ERR_ARG;
       t.vecs_per_thread = value;
       return RECOVER_OK;
     case 1:
@@ -611,7 +615,7 @@ int recover_set_tuning(int key, int value) {
     case 3:
     case 4:
     case 5:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return RECOVER_ERR_ARG;
+      if (value != 1 && value != 2 && value != 4) return RECOVER_ERR_ARG;
       (key == 3 ? t.reduce_vecs : key == 4 ? t.adamw_vecs : t.copy_vecs) = value;
       return RECOVER_OK;
   }

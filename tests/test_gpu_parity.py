@@ -211,9 +211,9 @@ def test_launch_shapes_do_not_change_the_bits():
     g = grads_np(11, N, 1e-3, False)
     ref = None
     try:
-        for U in (1, 2, 4, 8):
-            for nt, cap, xcd in ((1, 0, 1), (0, 0, 0), (1, 3, 0), (0, 2, 1)):
-                for key, val in ((0, U), (3, U), (4, U), (5, U), (1, nt), (2, cap), (6, xcd)):
+        for U in (1, 2, 4):
+            for nt, cap, xcd, T in ((1, 0, 1, 64), (0, 0, 0, 256), (1, 3, 0, 64), (0, 2, 1, 256)):
+                for key, val in ((0, U), (3, U), (4, U), (5, U), (1, nt), (2, cap), (6, xcd), (7, T)):
                     assert B.recover_set_tuning(key, val) == 0
                 _, s, eng = make_pair(4, 2, OFF, False, seed=11)
                 run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={1: 1}, fidelity_k=2)
@@ -221,9 +221,9 @@ def test_launch_shapes_do_not_change_the_bits():
                 if ref is None:
                     ref = cur
                 for x, y in zip(ref, cur):
-                    assert torch.equal(x, y), (U, nt, cap, xcd)
+                    assert torch.equal(x, y), (U, nt, cap, xcd, T)
     finally:
-        for key, val in ((0, 1), (1, 1), (2, 0), (3, 1), (4, 4), (5, 1), (6, 1)):      # the defaults
+        for key, val in ((0, 1), (1, 1), (2, 0), (3, 1), (4, 1), (5, 1), (6, 0), (7, 64)):      # the defaults
             B.recover_set_tuning(key, val)
 
 
