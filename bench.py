@@ -27,9 +27,19 @@ HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
 POOL = 4
 
 
-def workload():
+WORKLOAD_TEXT = {
+    1: "configs[0] tiny: 1,048,576 fp32 elements, R=4, M=8 (cache- and launch-bound, not an HBM measurement)",
+    2: "configs[1] GPT-2-small-sized shard: 123,589,632 fp32 elements in 148 tensors, R=8 replicas, "
+       "M=32 microbatches/iteration, failure-free iteration",
+    3: "configs[2] Llama-3-8B 1/8 HSDP shard: 1,003,749,376 elements in 30 tensors, bf16 gradients, R=8, M=64",
+    4: "configs[3] heavy attrition shape: 100,663,296 fp32 elements in 12 tensors, R=64, M=128",
+    5: "configs[4] Llama-70B-like 1/16 shard: 1,978,662,912 elements in 259 tensors, bf16 gradients, R=4, M=16",
+}
+
+
+def workload(k=2):
     from paper_2605_11215_amd.workloads import CONFIGS
-    return CONFIGS[2]
+    return CONFIGS[k]
 
 
 def bytes_per_elem(W, M, s_g, R_c):
@@ -70,7 +80,7 @@ def cpu_baseline(c, pool_slices, iters):
         p.adamw_step(**HP)
         p.advance()
     dt = time.perf_counter() - t0
-    b = bytes_per_elem(W, W * G, 4, W)["total"]
+    b = bytes_per_elem(W, W * G, 2 if c["bf16"] else 4, W)["total"]
     return dict(value=b * n * iters / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
                 sample="%d failure-free iterations of the same workload on a contiguous slice of %d elements "
                        "(oracle.proto.Proto, fp32, NumPy, one thread; %.1f s)" % (iters, n, dt),
@@ -85,6 +95,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-slice", type=int, default=1 << 24)
     ap.add_argument("--cpu-iters", type=int, default=16)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="which of the five configs to time (default 2 = the headline workload, configs[1])")
     ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -104,15 +116,17 @@ def main():
         k, v = kv.split("=")
         assert B.recover_set_tuning(int(k), int(v)) == 0, kv
 
-    c = workload()
+    c = workload(a.workload)
+    s_g = 2 if c["bf16"] else 4
     W, G, off = c["W"], c["G"], c["off"]
     N, M = off[-1], c["W"] * c["G"]
     T = len(off) - 1
     torch.cuda.set_device(0)
     sh = B.Shard(W, G, off, device="cuda:0", snapshots=True)
     synth.fill_device(sh.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=N)
-    pool = [synth.fill_device(torch.empty(N, dtype=torch.float32, device="cuda:0"), c["seed"], S.TAG_GRAD, j, 0,
-                              c["scale"]) for j in range(POOL)]
+    gdt, gcode = (torch.bfloat16, B.BF16) if c["bf16"] else (torch.float32, B.F32)
+    pool = [synth.fill_device(torch.empty(N, dtype=gdt, device="cuda:0"), c["seed"], S.TAG_GRAD, j, 0,
+                              c["scale"], c["kind"]) for j in range(POOL)]
     gptr = [g.data_ptr() for g in pool]
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream().cuda_stream
@@ -125,13 +139,13 @@ def main():
         if e:
             e[0].record()
         for r in range(W):                                    # k = 0: overwrite variant
-            rc = B.recover_accumulate(ctx, r, r, gptr[r % POOL], B.F32, 0, T, stream)
+            rc = B.recover_accumulate(ctx, r, r, gptr[r % POOL], gcode, 0, T, stream)
             assert rc == 0, rc
         if e:
             e[1].record()
         for k in range(1, G):                                 # read-modify-write variant
             for r in range(W):
-                rc = B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], B.F32, 0, T, stream)
+                rc = B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream)
                 assert rc == 0, rc
         if e:
             e[2].record()
@@ -158,12 +172,12 @@ def main():
     dt = time.perf_counter() - t0
     ms = dt * 1e3 / a.steps
 
-    bpe = bytes_per_elem(W, M, 4, W)
+    bpe = bytes_per_elem(W, M, s_g, W)
     gbs = bpe["total"] * N / (dt / a.steps) / 1e9
     phase = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]     # ms per iteration
     n_rmw = (G - 1) * W
     rmw_ms = phase[1] / n_rmw
-    k_gbs = dict(accumulate_first=W * 8 * N / phase[0] / 1e6, accumulate_rmw=12 * N / rmw_ms / 1e6,
+    k_gbs = dict(accumulate_first=W * (s_g + 4) * N / phase[0] / 1e6, accumulate_rmw=(s_g + 8) * N / rmw_ms / 1e6,
                  reduce=bpe["reduce"] * N / phase[2] / 1e6, adamw=28 * N / phase[3] / 1e6)
 
     # the same iteration with a snapshot of every replica before the reduction (Alg. 1 lines 9-10)
@@ -183,8 +197,7 @@ def main():
         "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "configs[1] GPT-2-small-sized shard: 123,589,632 fp32 elements in 148 tensors, "
-                               "R=8 replicas, M=32 microbatches/iteration, failure-free iteration",
+        "config": {"workload": WORKLOAD_TEXT[a.workload], "grad_dtype": "bf16" if c["bf16"] else "f32",
                    "replicas": W, "microbatches": M, "n_elems": N, "n_tensors": T,
                    "bytes_per_elem": bpe["total"], "grad_pool_buffers": POOL},
         "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
@@ -192,14 +205,14 @@ def main():
         "kernel_GBps": k_gbs,
         "phase_ms": dict(accumulate_first=phase[0], accumulate_rmw=phase[1], reduce=phase[2], adamw=phase[3]),
         "with_snapshot": with_snapshot,
-        "roofline": {"bound": "hbm", "kernel": "k_accumulate<float, RMW>", "achieved": k_gbs["accumulate_rmw"],
+        "roofline": {"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % ("bf16" if c["bf16"] else "float"), "achieved": k_gbs["accumulate_rmw"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
-                     "traffic": read_traffic(), "bytes_per_launch": 12 * N, "avg_launch_ms": rmw_ms,
+                     "traffic": read_traffic() if a.workload == 2 else None, "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,
                      "launches_timed": n_rmw * len(marks)},
     }
     if not a.no_cpu_baseline:
         n = min(a.cpu_slice, N)
-        slices = [g[:n].cpu().numpy() for g in pool]
+        slices = [g[:n].float().cpu().numpy() for g in pool]
         out["cpu_baseline"] = cpu_baseline(c, slices, a.cpu_iters)
     sh.close()
     print(json.dumps(out))
