@@ -25,8 +25,13 @@
  * 16-byte aligned, and is never freed, reallocated or synchronised by the library.  Device
  * work is enqueued on the `hip_stream` argument (a hipStream_t, NULL = the default stream)
  * and the calls return without waiting for it; host bookkeeping is updated at call time, so
- * all calls on one context must come from one thread at a time and its streams must be
- * ordered by the caller.  recover_policy_adjust and the query calls touch no device memory.
+ * all calls on one context must come from one thread at a time.  Calls on one context may use
+ * different streams: each call's device work is ordered after the previous call's by an event
+ * (no host wait), so e.g. recover_restore can run on a side stream while the caller's own
+ * kernels keep the main stream busy, and the next recover_accumulate waits for the rewind
+ * (the non-blocking restoration of Sec. 4.2).  Work of the CALLER that reads or writes the
+ * context's buffers must be ordered by the caller.  recover_policy_adjust and the query calls
+ * touch no device memory.
  *
  * Errors.  Every call returns RECOVER_OK (0), RECOVER_SKIPPED (1, nothing enqueued, not an
  * error) or a negative code; nothing throws or aborts.  After any negative return other than

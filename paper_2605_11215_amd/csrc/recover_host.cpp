@@ -49,6 +49,12 @@ struct recover_ctx {
 
   long step = 0;  // optimiser steps taken
   std::string err;
+
+  // Stream ordering: device calls on one context may come on different streams (the rewind of
+  // Alg. 5 runs on a side stream); each call is ordered after the previous one with an event.
+  hipStream_t last_stream = nullptr;
+  bool have_last_stream = false;
+  hipEvent_t order_event = nullptr;
 };
 
 static std::string g_init_err;
@@ -142,6 +148,22 @@ static void fill_decision(const recover_ctx *c, recover_decision *d, bool at_bou
   }
 }
 
+// Orders the work about to be enqueued on `s` after the context's previous device call if that
+// call used another stream: record an event there, make `s` wait for it.  No host wait.
+static int order_after_previous(recover_ctx *c, hipStream_t s, const char *who) {
+  if (c->host_only) return RECOVER_OK;
+  if (c->have_last_stream && c->last_stream != s) {
+    hipError_t he = hipSuccess;
+    if (!c->order_event) he = hipEventCreateWithFlags(&c->order_event, hipEventDisableTiming);
+    if (he == hipSuccess) he = hipEventRecord(c->order_event, c->last_stream);
+    if (he == hipSuccess) he = hipStreamWaitEvent(s, c->order_event, 0);
+    if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "%s: stream ordering: %s", who, hipGetErrorString(he));
+  }
+  c->last_stream = s;
+  c->have_last_stream = true;
+  return RECOVER_OK;
+}
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 extern "C" {
@@ -219,6 +241,7 @@ int recover_init(const recover_config *cfg, recover_ctx **out) {
 }
 
 int recover_destroy(recover_ctx *c) {
+  if (c && c->order_event) (void)hipEventDestroy(c->order_event);
   delete c;
   return RECOVER_OK;
 }
@@ -255,6 +278,7 @@ int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, 
   for (int b = tb; b < te; ++b)
     if (cnt[b] != k || sum[b])
       return fail(c, RECOVER_ERR_STATE, "accumulate: tensor %d of replica %d cannot take this microbatch", b, r);
+  if (int e = order_after_previous(c, (hipStream_t)stream, "accumulate")) return e;
   if (!c->host_only) {
     hipError_t he = recover::launch_accumulate(c->acc[r], grad, dtype == RECOVER_BF16, k == 0, (size_t)c->off[tb],
                                                (size_t)c->off[te], (hipStream_t)stream);
@@ -288,6 +312,7 @@ int recover_snapshot(recover_ctx *c, int replica, int tb, int te, void *stream) 
       if (c->holds_sum[(size_t)r * c->T + b])
         return fail(c, RECOVER_ERR_STATE, "snapshot: tensor %d of replica %d already holds a reduced sum", b, r);
   }
+  if (int e = order_after_previous(c, (hipStream_t)stream, "snapshot")) return e;
   for (int r = 0; r < c->W; ++r) {
     if ((replica >= 0 && r != replica) || !alive(c, r)) continue;
     if (!c->host_only) {
@@ -327,6 +352,7 @@ int recover_restore(recover_ctx *c, int replica, int stale_only, void *stream) {
     if (any && !even)
       return fail(c, RECOVER_ERR_STATE, "restore: rewind would leave replica %d between microbatches", r);
   }
+  if (int e = order_after_previous(c, (hipStream_t)stream, "restore")) return e;
   for (int r = 0; r < c->W; ++r) {
     if ((replica >= 0 && r != replica) || !alive(c, r)) continue;
     bool any = false;
@@ -504,6 +530,7 @@ int recover_reduce(recover_ctx *c, int tb, int te, uint32_t flags, void *stream)
         return fail(c, RECOVER_ERR_STATE, "reduce: tensor %d was already reduced in place", b);
   const int divisor = c->adaptive ? finished_by_contributors(c) : c->B;
   if (divisor <= 0) return fail(c, RECOVER_ERR_STATE, "reduce: nothing has been contributed");
+  if (int e = order_after_previous(c, (hipStream_t)stream, "reduce")) return e;
   // Tensors with the same contributor set share a launch.
   for (int b = tb; b < te;) {
     recover::ReduceArgs a;
@@ -559,6 +586,7 @@ int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float
                   c->red_total[b], want);
   }
   const long t = c->step + 1;
+  if (int e = order_after_previous(c, (hipStream_t)stream, "adamw_step")) return e;
   if (!c->host_only) {
     const double b1 = beta1, b2 = beta2;
     const double bc1 = 1.0 - pow(b1, (double)t), bc2 = 1.0 - pow(b2, (double)t);

@@ -252,3 +252,42 @@ def test_adaptive_policy_divides_by_the_committed_count():
     b = run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={2: 1})
     assert a["ids"] == b["ids"] and sum(len(v) for v in b["ids"].values()) == 6
     compare_iteration(o32, s, N, before)
+
+
+def test_nonblocking_restore_on_a_side_stream_is_ordered_by_the_library():
+    """Sec. 4.2 non-blocking restoration: the rewind runs on a side stream, snapshots on another,
+    while the main stream is held busy; the context orders its own calls with events, so the
+    result equals the single-stream run bit for bit."""
+    torch = torch_()
+    off = [0, 3000001, 3000004, 8388611]
+    N = off[-1]
+    g = grads_np(19, N, 1e-3, False)
+
+    class Streamed(HipEngine):
+        def __init__(self, shard):
+            super().__init__(shard)
+            self.side, self.side2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def reduce(self, tb=0, te=None, inplace=False):
+            if inplace:
+                torch.cuda._sleep(100_000_000)              # hold the main stream: ~50 ms
+            return self.s.reduce(tb, te, inplace)
+
+        def restore(self, r=None, stale_only=True):
+            with torch.cuda.stream(self.side):
+                self.s.restore(r, stale_only)
+
+        def snapshot(self, r=None, tb=0, te=None):
+            with torch.cuda.stream(self.side2):
+                self.s.snapshot(r, tb, te)
+
+    results = []
+    for cls in (HipEngine, Streamed):
+        _, s, _ = make_pair(6, 2, off, False, seed=19)
+        eng = cls(s)
+        run_iteration(eng, view_hip, 0, g, 6, hp=hp32(), dying={5: 2}, fidelity_k=2)
+        run_iteration(eng, view_hip, 1, g, 6, hp=hp32(), dying={1: 1}, fidelity_k=3, snapshot_every=True)
+        torch.cuda.synchronize()
+        results.append([x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)] + [a.clone() for a in s.acc])
+    for x, y in zip(*results):
+        assert torch.equal(x, y)
