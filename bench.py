@@ -133,28 +133,35 @@ def main():
     ctx = sh.ctx
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def iteration(marks=None, snapshot=False):
-        """One failure-free iteration.  marks: list receiving event pairs per phase."""
+    def iteration(marks=None, snapshot=False, fused=False, snapshot_every=False):
+        """One failure-free iteration.  marks: list receiving event pairs per phase.  fused: the one-pass
+        reduce+AdamW call; snapshot_every: the one-pass accumulate+snapshot call for every microbatch."""
+        acc_call = B.recover_accumulate_snapshot if snapshot_every else B.recover_accumulate
         e = [ev() for _ in range(5)] if marks is not None else None
         if e:
             e[0].record()
         for r in range(W):                                    # k = 0: overwrite variant
-            rc = B.recover_accumulate(ctx, r, r, gptr[r % POOL], gcode, 0, T, stream)
+            rc = acc_call(ctx, r, r, gptr[r % POOL], gcode, 0, T, stream)
             assert rc == 0, rc
         if e:
             e[1].record()
         for k in range(1, G):                                 # read-modify-write variant
             for r in range(W):
-                rc = B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream)
+                rc = acc_call(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream)
                 assert rc == 0, rc
         if e:
             e[2].record()
         if snapshot:
             assert B.recover_snapshot(ctx, -1, 0, T, stream) == 0
-        assert B.recover_reduce(ctx, 0, T, 0, stream) == 0
-        if e:
-            e[3].record()
-        assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], stream) == 0
+        if fused:
+            assert B.recover_reduce_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
+                                               0, stream) == 0
+        else:
+            assert B.recover_reduce(ctx, 0, T, 0, stream) == 0
+            if e:
+                e[3].record()
+            assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
+                                        stream) == 0
         if e:
             e[4].record()
             marks.append(e)
@@ -193,6 +200,27 @@ def main():
     with_snapshot = dict(ms_per_step=dts * 1e3, bytes_per_elem=bpe["total"] + 8 * W,
                          GBps=(bpe["total"] + 8 * W) * N / dts / 1e9)
 
+    def timed(n, **kw):
+        for _ in range(2):
+            iteration(**kw)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            iteration(**kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    # one-pass variants: reduce+AdamW without writing the gradient (4 R_c + 24 B/element), and
+    # accumulate+snapshot at every microbatch (s_g + 12 resp. s_g + 8 instead of s_g + 8 + 8 resp. s_g + 4 + 8)
+    dtf = timed(ns, fused=True)
+    b_fused = bpe["accumulate"] + 4 * W + 24
+    fused = dict(ms_per_step=dtf * 1e3, bytes_per_elem=b_fused, GBps=b_fused * N / dtf / 1e9,
+                 microbatches_per_s=M / dtf)
+    dte = timed(ns, fused=True, snapshot_every=True)
+    b_every = W * (s_g + 8) + (M - W) * (s_g + 12) + 4 * W + 24
+    every = dict(ms_per_step=dte * 1e3, bytes_per_elem=b_every, GBps=b_every * N / dte / 1e9,
+                 microbatches_per_s=M / dte)
+
     out = {
         "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
@@ -205,6 +233,8 @@ def main():
         "kernel_GBps": k_gbs,
         "phase_ms": dict(accumulate_first=phase[0], accumulate_rmw=phase[1], reduce=phase[2], adamw=phase[3]),
         "with_snapshot": with_snapshot,
+        "fused_reduce_adamw": fused,
+        "fused_snapshot_every_microbatch": every,
         "roofline": {"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % ("bf16" if c["bf16"] else "float"), "achieved": k_gbs["accumulate_rmw"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
                      "traffic": read_traffic() if a.workload == 2 else None, "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,

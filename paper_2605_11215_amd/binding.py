@@ -21,7 +21,10 @@ FLAG_ADAPTIVE, FLAG_ANY_ORDER, FLAG_HOST_ONLY = 1, 2, 4
 REDUCE_INPLACE = 1
 MAX_REPLICAS = 64
 
-EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_snapshot", "recover_restore",
+FUSED_WRITE_GRAD = 1
+
+EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_accumulate_snapshot",
+           "recover_reduce_adamw_step", "recover_snapshot", "recover_restore",
            "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
            "recover_committed_ids", "recover_last_error", "recover_set_tuning"]
 
@@ -61,6 +64,8 @@ def lib():
         L.recover_init.argtypes = [C.POINTER(Config), C.POINTER(P)]
         L.recover_destroy.argtypes = [P]
         L.recover_accumulate.argtypes = [P, I, U32, VP, I, I, I, VP]
+        L.recover_accumulate_snapshot.argtypes = [P, I, U32, VP, I, I, I, VP]
+        L.recover_reduce_adamw_step.argtypes = [P, F, F, F, F, F, U32, VP]
         L.recover_snapshot.argtypes = [P, I, I, I, VP]
         L.recover_restore.argtypes = [P, I, I, VP]
         L.recover_policy_adjust.argtypes = [P, C.POINTER(C.c_int32), I, C.POINTER(Decision)]
@@ -120,6 +125,15 @@ def recover_destroy(ctx):
 def recover_accumulate(ctx, replica, global_mb_id, grad, dtype, tensor_begin, tensor_end, stream=0):
     return lib().recover_accumulate(ctx, replica, global_mb_id, grad or None, dtype, tensor_begin, tensor_end,
                                     stream or None)
+
+
+def recover_accumulate_snapshot(ctx, replica, global_mb_id, grad, dtype, tensor_begin, tensor_end, stream=0):
+    return lib().recover_accumulate_snapshot(ctx, replica, global_mb_id, grad or None, dtype, tensor_begin,
+                                             tensor_end, stream or None)
+
+
+def recover_reduce_adamw_step(ctx, lr, beta1, beta2, eps, weight_decay, flags=0, stream=0):
+    return lib().recover_reduce_adamw_step(ctx, lr, beta1, beta2, eps, weight_decay, flags, stream or None)
 
 
 def recover_snapshot(ctx, replica, tensor_begin, tensor_end, stream=0):
@@ -222,9 +236,9 @@ class Shard:
     def _stream(self):
         return 0 if self.host_only else self.torch.cuda.current_stream().cuda_stream
 
-    def accumulate(self, r, mb_id, g, tb=0, te=None):
+    def accumulate(self, r, mb_id, g, tb=0, te=None, snapshot=False):
         """g: a flat torch tensor on the device (float32 or bfloat16), or None on a host-only context.
-        Returns False if the quota was already met."""
+        snapshot=True takes the fused accumulate+snapshot call.  Returns False if the quota was already met."""
         te = self.T if te is None else te
         if self.host_only:
             ptr, dt = 0, F32
@@ -232,7 +246,8 @@ class Shard:
             dt = BF16 if g.dtype == self.torch.bfloat16 else F32
             assert g.is_contiguous() and g.numel() >= self.N
             ptr = g.data_ptr()
-        return check(recover_accumulate(self.ctx, r, mb_id, ptr, dt, tb, te, self._stream()), self.ctx) == OK
+        f = recover_accumulate_snapshot if snapshot else recover_accumulate
+        return check(f(self.ctx, r, mb_id, ptr, dt, tb, te, self._stream()), self.ctx) == OK
 
     def snapshot(self, r=None, tb=0, te=None):
         te = self.T if te is None else te
@@ -257,6 +272,10 @@ class Shard:
 
     def adamw_step(self, lr, beta1, beta2, eps, weight_decay):
         check(recover_adamw_step(self.ctx, lr, beta1, beta2, eps, weight_decay, self._stream()), self.ctx)
+
+    def reduce_adamw_step(self, lr, beta1, beta2, eps, weight_decay, write_grad=False):
+        check(recover_reduce_adamw_step(self.ctx, lr, beta1, beta2, eps, weight_decay,
+                                        FUSED_WRITE_GRAD if write_grad else 0, self._stream()), self.ctx)
 
     def query(self):
         code, d = recover_query(self.ctx, self.W)

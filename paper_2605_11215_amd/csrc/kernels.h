@@ -31,12 +31,18 @@ struct ReduceArgs {
   float divisor;
 };
 
-hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bool first, size_t begin,
+// snap != nullptr: the new accumulator value is stored to snap as well (accumulate + snapshot in one pass)
+hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool grad_is_bf16, bool first, size_t begin,
                              size_t end, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s);
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s);
 hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n,
                         float decay_mul, float beta1, float one_minus_beta1, float beta2,
                         float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps, hipStream_t s);
+
+hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v, uint16_t *p_bf16, bool write_grad,
+                               size_t begin, size_t end, float decay_mul, float beta1, float one_minus_beta1,
+                               float beta2, float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps,
+                               hipStream_t s);
 
 }  // namespace recover

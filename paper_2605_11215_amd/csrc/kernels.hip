@@ -82,10 +82,11 @@ __device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to
 // ---------------------------------------------------------------------------------------------
 // accumulate: acc[i] = acc[i] + widen(g[i]);  FIRST: acc[i] = (+0) + widen(g[i])
 // ---------------------------------------------------------------------------------------------
-template <typename G, int T, int U, bool NT, bool FIRST>
-__global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, const G *__restrict__ g,
-                                                         Span sp, size_t ntiles, int xcd_chunked) {
+template <typename G, int T, int U, bool NT, bool FIRST, bool SNAP>
+__global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, float *__restrict__ snap,
+                                                  const G *__restrict__ g, Span sp, size_t ntiles, int xcd_chunked) {
   f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
+  f32x4 *s4 = reinterpret_cast<f32x4 *>(snap + sp.vbegin);
   const G *gv = g + sp.vbegin;
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
   size_t first = blockIdx.x, stride = gridDim.x;
@@ -96,30 +97,31 @@ __global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, const
   for (size_t tile = first; tile < ntiles; tile += stride) {
     const size_t base = tile * size_t(T * U) + threadIdx.x;
     f32x4 x[U], a[U];
-    if (base + size_t(T) * (U - 1) < sp.nvec) {
+    bool ok[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) x[u] = load_grad<NT>(gv, base + size_t(T) * u);
-      if (!FIRST) {
+    for (int u = 0; u < U; ++u) ok[u] = base + size_t(T) * u < sp.nvec;
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld<NT>(a4 + base + size_t(T) * u);
-      }
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) x[u] = load_grad<NT>(gv, base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u) st<NT>(a4 + base + size_t(T) * u, (FIRST ? zero : a[u]) + x[u]);
-    } else {
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) a[u] = FIRST ? zero : ld<NT>(a4 + base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const size_t i = base + size_t(T) * u;
-        if (i < sp.nvec) {
-          f32x4 xv = load_grad<NT>(gv, i);
-          f32x4 av = FIRST ? zero : ld<NT>(a4 + i);
-          st<NT>(a4 + i, av + xv);
-        }
+    for (int u = 0; u < U; ++u) {
+      if (ok[u]) {
+        const f32x4 r = a[u] + x[u];
+        st<NT>(a4 + base + size_t(T) * u, r);
+        if (SNAP) st<NT>(s4 + base + size_t(T) * u, r);
       }
     }
   }
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t i = ragged_index(sp, threadIdx.x);
-    if (i < sp.end) acc[i] = (FIRST ? 0.f : acc[i]) + load_grad1(g, i);
+    if (i < sp.end) {
+      const float r = (FIRST ? 0.f : acc[i]) + load_grad1(g, i);
+      acc[i] = r;
+      if (SNAP) snap[i] = r;
+    }
   }
 }
 
@@ -243,11 +245,14 @@ struct AdamArgs {
   float decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps;
 };
 
+// The fused multiply-adds are written out so that every kernel that inlines this function rounds
+// in the same places.
 __device__ inline void adam1(float &p, float &m, float &v, float g, const AdamArgs &h) {
-  m = h.beta1 * m + h.one_minus_beta1 * g;
-  v = h.beta2 * v + h.one_minus_beta2 * (g * g);
-  float denom = sqrtf(v) * h.inv_sqrt_bc2 + h.eps;
-  p = p * h.decay_mul - h.step_size * (m / denom);
+#pragma clang fp contract(off)
+  m = __builtin_fmaf(h.beta1, m, h.one_minus_beta1 * g);
+  v = __builtin_fmaf(h.beta2, v, h.one_minus_beta2 * (g * g));
+  const float denom = __builtin_fmaf(sqrtf(v), h.inv_sqrt_bc2, h.eps);
+  p = __builtin_fmaf(-h.step_size, m / denom, p * h.decay_mul);
 }
 
 __device__ inline uint32_t f32_to_bf16_rne(float x) {
@@ -328,6 +333,69 @@ __global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__res
 }
 
 // ---------------------------------------------------------------------------------------------
+// fused reduce + AdamW: the contributor sum of k_reduce, its division, and the update of k_adamw in
+// one pass; the gradient goes to HBM only if WRITE_GRAD.  4 R_c + 24 (+4) bytes per element.
+// ---------------------------------------------------------------------------------------------
+template <int T, bool NT, bool WRITE_GRAD, bool BF16OUT>
+__global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, float *__restrict__ p, float *__restrict__ m,
+                                                    float *__restrict__ v, uint16_t *__restrict__ pb, Span sp,
+                                                    AdamArgs h) {
+  const size_t i = size_t(blockIdx.x) * T + threadIdx.x;
+  if (i < sp.nvec) {
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    int r = 0;
+    if (a.n_src > 0) {
+      sum = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + i);
+      r = 1;
+    }
+    for (; r + 1 < a.n_src; r += 2) {
+      const f32x4 t0 = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + i);
+      const f32x4 t1 = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r + 1] + sp.vbegin) + i);
+      sum = (sum + t0) + t1;
+    }
+    if (r < a.n_src) sum = sum + ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + i);
+    f32x4 *p4 = reinterpret_cast<f32x4 *>(p + sp.vbegin) + i;
+    f32x4 *m4 = reinterpret_cast<f32x4 *>(m + sp.vbegin) + i;
+    f32x4 *v4 = reinterpret_cast<f32x4 *>(v + sp.vbegin) + i;
+    f32x4 pv = ld<NT>(p4), mv = ld<NT>(m4), vv = ld<NT>(v4), q;
+#pragma unroll
+    for (int l = 0; l < 4; ++l) {
+      q[l] = sum[l] / a.divisor;
+      float pp = pv[l], mm = mv[l], v1 = vv[l];
+      adam1(pp, mm, v1, q[l], h);
+      pv[l] = pp;
+      mv[l] = mm;
+      vv[l] = v1;
+    }
+    st<NT>(p4, pv);
+    st<NT>(m4, mv);
+    st<NT>(v4, vv);
+    if (WRITE_GRAD) st<NT>(reinterpret_cast<f32x4 *>(a.out + sp.vbegin) + i, q);
+    if (BF16OUT) {
+      u32x2 w;
+      w.x = f32_to_bf16_rne(pv.x) | (f32_to_bf16_rne(pv.y) << 16);
+      w.y = f32_to_bf16_rne(pv.z) | (f32_to_bf16_rne(pv.w) << 16);
+      st<NT>(reinterpret_cast<u32x2 *>(pb + sp.vbegin) + i, w);
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 8) {
+    const size_t e = ragged_index(sp, threadIdx.x);
+    if (e < sp.end) {
+      float sum = 0.f;
+      for (int r = 0; r < a.n_src; ++r) sum = (r == 0) ? a.src[r][e] : sum + a.src[r][e];
+      const float q = sum / a.divisor;
+      float pp = p[e], mm = m[e], v1 = v[e];
+      adam1(pp, mm, v1, q, h);
+      p[e] = pp;
+      m[e] = mm;
+      v[e] = v1;
+      if (WRITE_GRAD) a.out[e] = q;
+      if (BF16OUT) pb[e] = (uint16_t)f32_to_bf16_rne(pp);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
 static bool grid_for(size_t nvec, int T, int U, unsigned *grid, size_t *ntiles) {
@@ -366,8 +434,8 @@ static void with_shape(int T, int U, bool NT, F &&f) {
     with_nt(Int<64>{});
 }
 
-hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bool first, size_t begin, size_t end,
-                             hipStream_t s) {
+hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool grad_is_bf16, bool first, size_t begin,
+                             size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
   const int Uv = tuning().vecs_per_thread, Tv = tuning().threads;
@@ -379,19 +447,24 @@ hipError_t launch_accumulate(float *acc, const void *grad, bool grad_is_bf16, bo
   with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
     constexpr int T = decltype(t)::value, U = decltype(u)::value;
     constexpr bool NT = decltype(nt)::value;
-    if (grad_is_bf16) {
-      const uint16_t *g = static_cast<const uint16_t *>(grad);
-      if (first)
-        hipLaunchKernelGGL((k_accumulate<uint16_t, T, U, NT, true>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
-      else
-        hipLaunchKernelGGL((k_accumulate<uint16_t, T, U, NT, false>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
-    } else {
-      const float *g = static_cast<const float *>(grad);
-      if (first)
-        hipLaunchKernelGGL((k_accumulate<float, T, U, NT, true>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
-      else
-        hipLaunchKernelGGL((k_accumulate<float, T, U, NT, false>), dim3(grid), dim3(T), 0, s, acc, g, sp, ntiles, xc);
-    }
+    auto go = [&](auto gptr, auto is_first, auto with_snap) {
+      using GT = std::remove_cv_t<std::remove_pointer_t<decltype(gptr)>>;
+      hipLaunchKernelGGL((k_accumulate<GT, T, U, NT, decltype(is_first)::value, decltype(with_snap)::value>), dim3(grid),
+                         dim3(T), 0, s, acc, snap, gptr, sp, ntiles, xc);
+    };
+    auto pick = [&](auto gptr) {
+      if (first) {
+        if (snap) go(gptr, std::true_type{}, std::true_type{});
+        else go(gptr, std::true_type{}, std::false_type{});
+      } else {
+        if (snap) go(gptr, std::false_type{}, std::true_type{});
+        else go(gptr, std::false_type{}, std::false_type{});
+      }
+    };
+    if (grad_is_bf16)
+      pick(static_cast<const uint16_t *>(grad));
+    else
+      pick(static_cast<const float *>(grad));
   });
   return hipGetLastError();
 }
@@ -447,6 +520,33 @@ hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *
     else
       hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
   });
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v, uint16_t *p_bf16, bool write_grad,
+                               size_t begin, size_t end, float decay_mul, float beta1, float one_minus_beta1,
+                               float beta2, float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps,
+                               hipStream_t s) {
+  if (begin >= end) return hipSuccess;
+  const Span sp = make_span(begin, end);
+  const AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
+  const size_t tiles = (sp.nvec + 63) / 64;  // one tile per one-wavefront workgroup, no grid cap
+  if (tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+  const unsigned grid = tiles ? (unsigned)tiles : 1u;
+  auto go = [&](auto nt, auto wg, auto bf) {
+    hipLaunchKernelGGL((k_reduce_adamw<64, decltype(nt)::value, decltype(wg)::value, decltype(bf)::value>), dim3(grid),
+                       dim3(64), 0, s, a, p, m, v, p_bf16, sp, h);
+  };
+  auto with_bf = [&](auto nt, auto wg) {
+    if (p_bf16) go(nt, wg, std::true_type{});
+    else go(nt, wg, std::false_type{});
+  };
+  auto with_wg = [&](auto nt) {
+    if (write_grad) with_bf(nt, std::true_type{});
+    else with_bf(nt, std::false_type{});
+  };
+  if (tuning().nontemporal) with_wg(std::true_type{});
+  else with_wg(std::false_type{});
   return hipGetLastError();
 }
 

@@ -253,8 +253,8 @@ static int check_range(recover_ctx *c, int tb, int te, const char *who) {
   return RECOVER_OK;
 }
 
-int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, int dtype, int tb, int te,
-                       void *stream) {
+static int accumulate_impl(recover_ctx *c, int r, uint32_t mb_id, const void *grad, int dtype, int tb, int te,
+                           void *stream, bool with_snapshot) {
   if (!c) return RECOVER_ERR_ARG;
   if (r < 0 || r >= c->W) return fail(c, RECOVER_ERR_ARG, "accumulate: replica %d out of range", r);
   if (dtype != RECOVER_F32 && dtype != RECOVER_BF16) return fail(c, RECOVER_ERR_ARG, "accumulate: dtype %d", dtype);
@@ -263,6 +263,8 @@ int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, 
     if (!grad) return fail(c, RECOVER_ERR_ARG, "accumulate: NULL gradient");
     if (!aligned16(grad)) return fail(c, RECOVER_ERR_ALIGN, "accumulate: gradient not 16-byte aligned");
   }
+  if (with_snapshot && !c->have_snap)
+    return fail(c, RECOVER_ERR_NO_SNAPSHOT, "accumulate_snapshot: context has no snapshot buffers");
   if (c->pending_advance) return fail(c, RECOVER_ERR_STATE, "accumulate: policy advancement pending (Alg. 7)");
   if (!alive(c, r)) return fail(c, RECOVER_ERR_STATE, "accumulate: replica %d is dead", r);
   if (c->contributed[r] >= c->target[r]) return RECOVER_SKIPPED;
@@ -280,8 +282,9 @@ int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, 
       return fail(c, RECOVER_ERR_STATE, "accumulate: tensor %d of replica %d cannot take this microbatch", b, r);
   if (int e = order_after_previous(c, (hipStream_t)stream, "accumulate")) return e;
   if (!c->host_only) {
-    hipError_t he = recover::launch_accumulate(c->acc[r], grad, dtype == RECOVER_BF16, k == 0, (size_t)c->off[tb],
-                                               (size_t)c->off[te], (hipStream_t)stream);
+    hipError_t he = recover::launch_accumulate(c->acc[r], with_snapshot ? c->snap[r] : nullptr, grad,
+                                               dtype == RECOVER_BF16, k == 0, (size_t)c->off[tb], (size_t)c->off[te],
+                                               (hipStream_t)stream);
     if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "accumulate: %s", hipGetErrorString(he));
   }
   for (int b = tb; b < te; ++b) {
@@ -297,7 +300,25 @@ int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, 
     c->open_mb[r] = false;
     c->contributed[r] = k + 1;
   }
+  if (with_snapshot) {
+    for (int b = tb; b < te; ++b) {
+      const size_t i = (size_t)r * c->T + b;
+      c->snap_valid[i] = 1;
+      c->snap_eps[i] = c->eps;
+      c->snap_cnt[i] = c->cnt[i];
+    }
+  }
   return RECOVER_OK;
+}
+
+int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, int dtype, int tb, int te,
+                       void *stream) {
+  return accumulate_impl(c, r, mb_id, grad, dtype, tb, te, stream, false);
+}
+
+int recover_accumulate_snapshot(recover_ctx *c, int r, uint32_t mb_id, const void *grad, int dtype, int tb, int te,
+                                void *stream) {
+  return accumulate_impl(c, r, mb_id, grad, dtype, tb, te, stream, true);
 }
 
 int recover_snapshot(recover_ctx *c, int replica, int tb, int te, void *stream) {
@@ -518,25 +539,26 @@ int recover_policy_adjust(recover_ctx *c, const int32_t *failed, int n_failed, r
   return RECOVER_OK;
 }
 
-int recover_reduce(recover_ctx *c, int tb, int te, uint32_t flags, void *stream) {
-  if (!c) return RECOVER_ERR_ARG;
-  if (int e = check_range(c, tb, te, "reduce")) return e;
-  if (flags & ~RECOVER_REDUCE_INPLACE) return fail(c, RECOVER_ERR_ARG, "reduce: unknown flag");
-  if (c->quiesced) return RECOVER_SKIPPED;
-  const bool inplace = flags & RECOVER_REDUCE_INPLACE;
+// One launch of the reduction: tensors [b, e) share one contributor set.
+struct ReduceGroup {
+  int b, e;
+  recover::ReduceArgs a;
+};
+
+// Checks and plan of a reduction over tensors [tb, te): groups of adjacent tensors with the same
+// contributor set (majors and minors that hold at least one microbatch there).
+static int plan_reduce(recover_ctx *c, int tb, int te, bool inplace, std::vector<ReduceGroup> *groups, const char *who) {
   for (int b = tb; b < te; ++b)
     for (int r = 0; r < c->W; ++r)
       if (alive(c, r) && c->holds_sum[(size_t)r * c->T + b])
-        return fail(c, RECOVER_ERR_STATE, "reduce: tensor %d was already reduced in place", b);
+        return fail(c, RECOVER_ERR_STATE, "%s: tensor %d was already reduced in place", who, b);
   const int divisor = c->adaptive ? finished_by_contributors(c) : c->B;
-  if (divisor <= 0) return fail(c, RECOVER_ERR_STATE, "reduce: nothing has been contributed");
-  if (int e = order_after_previous(c, (hipStream_t)stream, "reduce")) return e;
-  // Tensors with the same contributor set share a launch.
+  if (divisor <= 0) return fail(c, RECOVER_ERR_STATE, "%s: nothing has been contributed", who);
   for (int b = tb; b < te;) {
-    recover::ReduceArgs a;
-    a.n_src = a.n_sum_dst = 0;
+    ReduceGroup g;
+    g.a.n_src = g.a.n_sum_dst = 0;
     for (int r = 0; r < c->W; ++r)
-      if (contributor(c, r) && c->cnt[(size_t)r * c->T + b] > 0) a.src[a.n_src++] = c->acc[r];
+      if (contributor(c, r) && c->cnt[(size_t)r * c->T + b] > 0) g.a.src[g.a.n_src++] = c->acc[r];
     int e = b + 1;
     for (; e < te; ++e) {
       bool same = true;
@@ -547,35 +569,88 @@ int recover_reduce(recover_ctx *c, int tb, int te, uint32_t flags, void *stream)
     }
     if (inplace)
       for (int r = 0; r < c->W; ++r)
-        if (alive(c, r)) a.sum_dst[a.n_sum_dst++] = c->acc[r];
-    a.out = c->grad_out;
-    a.divisor = (float)divisor;
-    if (!c->host_only) {
-      hipError_t he = recover::launch_reduce(a, (size_t)c->off[b], (size_t)c->off[e], (hipStream_t)stream);
-      if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "reduce: %s", hipGetErrorString(he));
-    }
-    for (int q = b; q < e; ++q) {
-      int total = 0;
-      for (int r = 0; r < c->W; ++r)
-        if (contributor(c, r)) total += c->cnt[(size_t)r * c->T + q];
-      c->red_eps[q] = c->eps;
-      c->red_total[q] = total;
-      c->red_dirty[q] = 0;
-      if (inplace)
-        for (int r = 0; r < c->W; ++r)
-          if (alive(c, r)) c->holds_sum[(size_t)r * c->T + q] = 1;
-    }
+        if (alive(c, r)) g.a.sum_dst[g.a.n_sum_dst++] = c->acc[r];
+    g.a.out = c->grad_out;
+    g.a.divisor = (float)divisor;
+    g.b = b;
+    g.e = e;
+    groups->push_back(g);
     b = e;
   }
   return RECOVER_OK;
 }
 
-int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
-                       void *stream) {
+static int microbatches_in(const recover_ctx *c, int tensor) {
+  int total = 0;
+  for (int r = 0; r < c->W; ++r)
+    if (contributor(c, r)) total += c->cnt[(size_t)r * c->T + tensor];
+  return total;
+}
+
+static void note_reduced(recover_ctx *c, const ReduceGroup &g, bool inplace) {
+  for (int q = g.b; q < g.e; ++q) {
+    c->red_eps[q] = c->eps;
+    c->red_total[q] = microbatches_in(c, q);
+    c->red_dirty[q] = 0;
+    if (inplace)
+      for (int r = 0; r < c->W; ++r)
+        if (alive(c, r)) c->holds_sum[(size_t)r * c->T + q] = 1;
+  }
+}
+
+int recover_reduce(recover_ctx *c, int tb, int te, uint32_t flags, void *stream) {
   if (!c) return RECOVER_ERR_ARG;
+  if (int e = check_range(c, tb, te, "reduce")) return e;
+  if (flags & ~RECOVER_REDUCE_INPLACE) return fail(c, RECOVER_ERR_ARG, "reduce: unknown flag");
+  if (c->quiesced) return RECOVER_SKIPPED;
+  const bool inplace = flags & RECOVER_REDUCE_INPLACE;
+  std::vector<ReduceGroup> groups;
+  if (int e = plan_reduce(c, tb, te, inplace, &groups, "reduce")) return e;
+  if (int e = order_after_previous(c, (hipStream_t)stream, "reduce")) return e;
+  for (const ReduceGroup &g : groups) {
+    if (!c->host_only) {
+      hipError_t he = recover::launch_reduce(g.a, (size_t)c->off[g.b], (size_t)c->off[g.e], (hipStream_t)stream);
+      if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "reduce: %s", hipGetErrorString(he));
+    }
+    note_reduced(c, g, inplace);
+  }
+  return RECOVER_OK;
+}
+
+static int check_hyper(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay) {
   if (!(lr >= 0.f) || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) ||
       !(weight_decay >= 0.f))
     return fail(c, RECOVER_ERR_ARG, "adamw_step: hyper-parameter out of range");
+  return RECOVER_OK;
+}
+
+// AdamW constants for step t, prepared in double.
+struct AdamConsts {
+  float decay_mul, one_minus_beta1, one_minus_beta2, step_size, inv_sqrt_bc2;
+};
+static AdamConsts adam_consts(long t, float lr, float beta1, float beta2, float weight_decay) {
+  const double b1 = beta1, b2 = beta2;
+  const double bc1 = 1.0 - pow(b1, (double)t), bc2 = 1.0 - pow(b2, (double)t);
+  AdamConsts k;
+  k.decay_mul = (float)(1.0 - (double)lr * (double)weight_decay);
+  k.one_minus_beta1 = (float)(1.0 - b1);
+  k.one_minus_beta2 = (float)(1.0 - b2);
+  k.step_size = (float)((double)lr / bc1);
+  k.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+  return k;
+}
+
+// The optimiser step has been enqueued: the iteration is committed (Alg. 1 line 24).
+static void commit_iteration(recover_ctx *c) {
+  c->step += 1;
+  c->pending_advance = c->crossed_boundary;
+  open_iteration(c);
+}
+
+int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
+                       void *stream) {
+  if (!c) return RECOVER_ERR_ARG;
+  if (int e = check_hyper(c, lr, beta1, beta2, eps, weight_decay)) return e;
   if (c->quiesced) return fail(c, RECOVER_ERR_STATE, "adamw_step: a failure is being handled (restore first)");
   const int want = c->adaptive ? finished_by_contributors(c) : c->B;
   for (int b = 0; b < c->T; ++b) {
@@ -585,20 +660,45 @@ int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float
       return fail(c, RECOVER_ERR_STATE, "adamw_step: tensor %d holds %d microbatches, Eq. 1 needs %d", b,
                   c->red_total[b], want);
   }
-  const long t = c->step + 1;
   if (int e = order_after_previous(c, (hipStream_t)stream, "adamw_step")) return e;
   if (!c->host_only) {
-    const double b1 = beta1, b2 = beta2;
-    const double bc1 = 1.0 - pow(b1, (double)t), bc2 = 1.0 - pow(b2, (double)t);
+    const AdamConsts k = adam_consts(c->step + 1, lr, beta1, beta2, weight_decay);
     hipError_t he = recover::launch_adamw(c->param, c->exp_avg, c->exp_avg_sq, c->grad_out, c->param_bf16, (size_t)c->N,
-                                          (float)(1.0 - (double)lr * (double)weight_decay), beta1, (float)(1.0 - b1),
-                                          beta2, (float)(1.0 - b2), (float)((double)lr / bc1),
-                                          (float)(1.0 / sqrt(bc2)), eps, (hipStream_t)stream);
+                                          k.decay_mul, beta1, k.one_minus_beta1, beta2, k.one_minus_beta2, k.step_size,
+                                          k.inv_sqrt_bc2, eps, (hipStream_t)stream);
     if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "adamw_step: %s", hipGetErrorString(he));
   }
-  c->step = t;
-  c->pending_advance = c->crossed_boundary;
-  open_iteration(c);
+  commit_iteration(c);
+  return RECOVER_OK;
+}
+
+int recover_reduce_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
+                              uint32_t flags, void *stream) {
+  if (!c) return RECOVER_ERR_ARG;
+  if (int e = check_hyper(c, lr, beta1, beta2, eps, weight_decay)) return e;
+  if (flags & ~RECOVER_FUSED_WRITE_GRAD) return fail(c, RECOVER_ERR_ARG, "reduce_adamw_step: unknown flag");
+  if (c->quiesced) return fail(c, RECOVER_ERR_STATE, "reduce_adamw_step: a failure is being handled (restore first)");
+  std::vector<ReduceGroup> groups;
+  if (int e = plan_reduce(c, 0, c->T, false, &groups, "reduce_adamw_step")) return e;
+  const int want = c->adaptive ? finished_by_contributors(c) : c->B;
+  for (int b = 0; b < c->T; ++b)
+    if (microbatches_in(c, b) != want)
+      return fail(c, RECOVER_ERR_STATE, "reduce_adamw_step: tensor %d holds %d microbatches, Eq. 1 needs %d", b,
+                  microbatches_in(c, b), want);
+  if (int e = order_after_previous(c, (hipStream_t)stream, "reduce_adamw_step")) return e;
+  const AdamConsts k = adam_consts(c->step + 1, lr, beta1, beta2, weight_decay);
+  for (const ReduceGroup &g : groups) {
+    if (!c->host_only) {
+      hipError_t he = recover::launch_reduce_adamw(g.a, c->param, c->exp_avg, c->exp_avg_sq, c->param_bf16,
+                                                   flags & RECOVER_FUSED_WRITE_GRAD, (size_t)c->off[g.b],
+                                                   (size_t)c->off[g.e], k.decay_mul, beta1, k.one_minus_beta1, beta2,
+                                                   k.one_minus_beta2, k.step_size, k.inv_sqrt_bc2, eps,
+                                                   (hipStream_t)stream);
+      if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "reduce_adamw_step: %s", hipGetErrorString(he));
+    }
+    note_reduced(c, g, false);
+  }
+  commit_iteration(c);
   return RECOVER_OK;
 }
 

@@ -18,15 +18,18 @@ def view_oracle(p):
 
 
 def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
-                  snapshot_every=False, hp=HP, on_sync=None):
+                  snapshot_every=False, hp=HP, on_sync=None, fuse=False):
     """One iteration of Alg. 1.
 
     dying        {replica: n}: the replica crashes having accumulated n microbatches; the
                  survivors learn of it at the synchronisation point (Sec. 3, iteration anatomy)
     fidelity_k   > 0: before the failure is detected, the first k tensors are snapshotted
                  and all-reduced in place under the old membership (failure case (c), Sec. 4.2)
+    fuse         use the engine's one-pass calls where it has them: accumulate+snapshot for
+                 snapshot_every, reduce+AdamW for the commit (same results as the separate calls)
     Returns dict(decisions=[...], ids={replica: [ids]}).
     """
+    fuse = fuse and hasattr(eng, "reduce_adamw_step")
     dying = dict(dying or {})
     crashed = set()
     decisions = []
@@ -42,8 +45,11 @@ def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
                     continue
                 if v["contributed"][r] < v["target"][r]:
                     mb = r + W_init * v["contributed"][r]
-                    eng.accumulate(r, mb, grad_of(t, mb))
-            if snapshot_every:
+                    if fuse and snapshot_every:
+                        eng.accumulate(r, mb, grad_of(t, mb), snapshot=True)
+                    else:
+                        eng.accumulate(r, mb, grad_of(t, mb))
+            if snapshot_every and not fuse:
                 for r in view(eng)["alive"]:
                     if r not in crashed:
                         eng.snapshot(r)
@@ -60,10 +66,14 @@ def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
         eng.snapshot(None)
         if on_sync:
             on_sync(eng)
-        eng.reduce()
+        if not fuse:
+            eng.reduce()
         break
     ids = eng_committed_ids(eng)
-    eng.adamw_step(**hp)
+    if fuse:
+        eng.reduce_adamw_step(write_grad=True, **hp)
+    else:
+        eng.adamw_step(**hp)
     decisions.append(eng.advance())
     return dict(decisions=decisions, ids=ids)
 

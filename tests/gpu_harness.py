@@ -26,7 +26,7 @@ class HipEngine:
     def __getattr__(self, k):
         return getattr(self.s, k)
 
-    def accumulate(self, r, mb, g, tb=0, te=None):
+    def accumulate(self, r, mb, g, tb=0, te=None, snapshot=False):
         torch = self.torch
         if isinstance(g, np.ndarray):
             if self.bf16:
@@ -36,7 +36,7 @@ class HipEngine:
             if h.numel() < 8:
                 h = torch.cat([h, torch.zeros(8, dtype=h.dtype, device=h.device)])
             g = h
-        return self.s.accumulate(r, mb, g, tb, te)
+        return self.s.accumulate(r, mb, g, tb, te, snapshot=snapshot)
 
 
 def device_grad_source(cfg, buf):

@@ -134,8 +134,8 @@ def test_protocol_bookkeeping_matches_oracle_call_by_call(static):
             def __getattr__(self, k):
                 return getattr(s, k)
 
-            def accumulate(self, r, mb, grad, tb=0, te=None):
-                return s.accumulate(r, mb, None, tb, te)
+            def accumulate(self, r, mb, grad, tb=0, te=None, snapshot=False):
+                return s.accumulate(r, mb, None, tb, te, snapshot=snapshot)
 
         h = HostOnly()
         for t in range(5):
@@ -147,7 +147,7 @@ def test_protocol_bookkeeping_matches_oracle_call_by_call(static):
                      for r in rng.choice(alive, nf, replace=False)}
             kw = dict(dying=dying, fidelity_k=int(rng.integers(0, 5)), snapshot_every=bool(rng.integers(0, 2)))
             a = run_iteration(o, view_oracle, t, lambda t, mb: g, W, **kw)
-            b = run_iteration(h, view_hip, t, lambda t, mb: None, W, **kw)
+            b = run_iteration(h, view_hip, t, lambda t, mb: None, W, fuse=bool(trial % 2), **kw)
             assert a["ids"] == b["ids"]
             assert len(a["decisions"]) == len(b["decisions"])
             for x, y in zip(a["decisions"], b["decisions"]):

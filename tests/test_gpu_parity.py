@@ -291,3 +291,36 @@ def test_nonblocking_restore_on_a_side_stream_is_ordered_by_the_library():
         results.append([x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)] + [a.clone() for a in s.acc])
     for x, y in zip(*results):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_fused_calls_give_the_bits_of_the_separate_calls(bf16):
+    """recover_accumulate_snapshot and recover_reduce_adamw_step against accumulate + snapshot and
+    reduce + adamw_step: every buffer identical, through failures, rewinds and an extended pass;
+    and the fused run against the oracle."""
+    torch = torch_()
+    N = OFF[-1]
+    g = grads_np(23, N, 1e-3, bf16)
+    o32, s_f, eng_f = make_pair(8, 2, OFF, bf16, seed=23)
+    _, s_u, eng_u = make_pair(8, 2, OFF, bf16, seed=23)
+    plan = [dict(), dict(dying={2: 1, 5: 0}, fidelity_k=3), dict(dying={0: 2}), dict()]
+    for t, kw in enumerate(plan):
+        before = state_of(s_f, N)
+        a = run_iteration(o32, view_oracle, t, g, 8, hp=hp32(), snapshot_every=True, **kw)
+        b = run_iteration(eng_f, view_hip, t, g, 8, hp=hp32(), snapshot_every=True, fuse=True, **kw)
+        c = run_iteration(eng_u, view_hip, t, g, 8, hp=hp32(), snapshot_every=True, fuse=False, **kw)
+        assert a["ids"] == b["ids"] == c["ids"]
+        for x, y in [(s_f.grad_out, s_u.grad_out), (s_f.param, s_u.param), (s_f.exp_avg, s_u.exp_avg),
+                     (s_f.exp_avg_sq, s_u.exp_avg_sq), (s_f.param_bf16, s_u.param_bf16)]:
+            assert torch.equal(x, y)
+        for r in b["ids"]:
+            assert torch.equal(s_f.acc[r], s_u.acc[r]) and torch.equal(s_f.snap[r], s_u.snap[r])
+        compare_iteration(o32, s_f, N, before)
+    # without the flag the gradient buffer is left alone
+    s_f.grad_out.fill_(7.0)
+    for r in view_hip(s_f)["alive"]:
+        while s_f.accumulate(r, 1000 + r + 8 * view_hip(s_f)["contributed"][r], torch.from_numpy(g(9, r)).cuda()
+                             if not bf16 else torch.from_numpy(g(9, r)).cuda().bfloat16()):
+            pass
+    s_f.reduce_adamw_step(**hp32())
+    assert float(s_f.grad_out.min()) == 7.0 == float(s_f.grad_out.max())
