@@ -221,6 +221,30 @@ def main():
     every = dict(ms_per_step=dte * 1e3, bytes_per_elem=b_every, GBps=b_every * N / dte / 1e9,
                  microbatches_per_s=M / dte)
 
+    # launch-bound shards: one accumulate_many launch per microbatch slot + the fused step (G + 1 launches)
+    def iteration_batched():
+        for k in range(G):
+            rc, _ = B.recover_accumulate_many(ctx, list(range(W)), [r + W * k for r in range(W)],
+                                              [gptr[(k * W + r) % POOL] for r in range(W)], gcode, stream)
+            assert rc == 0, rc
+        assert B.recover_reduce_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
+                                           0, stream) == 0
+        rc, _ = B.recover_policy_adjust(ctx, [], W)
+        assert rc == 0
+
+    batched = None
+    if a.workload == 1:
+        for _ in range(3):
+            iteration_batched()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(a.steps):
+            iteration_batched()
+        torch.cuda.synchronize()
+        dtb = (time.perf_counter() - t2) / a.steps
+        batched = dict(ms_per_step=dtb * 1e3, launches=G + 1, bytes_per_elem=b_fused, GBps=b_fused * N / dtb / 1e9,
+                       microbatches_per_s=M / dtb)
+
     out = {
         "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
@@ -235,6 +259,7 @@ def main():
         "with_snapshot": with_snapshot,
         "fused_reduce_adamw": fused,
         "fused_snapshot_every_microbatch": every,
+        "batched_launches": batched,
         "roofline": {"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % ("bf16" if c["bf16"] else "float"), "achieved": k_gbs["accumulate_rmw"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
                      "traffic": read_traffic() if a.workload == 2 else None, "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,

@@ -141,6 +141,15 @@ int recover_destroy(recover_ctx *ctx);
 int recover_accumulate(recover_ctx *ctx, int replica, uint32_t global_mb_id, const void *grad, int dtype,
                        int tensor_begin, int tensor_end, void *hip_stream);
 
+/* recover_accumulate over ALL tensors for n distinct replicas in ONE launch: pair i adds grads[i] (device,
+ * flat, `dtype`) as microbatch ids[i] into acc[replicas[i]].  `replicas`, `ids`, `grads`, `status_out` are host
+ * arrays of n entries; status_out (or NULL) receives RECOVER_OK or RECOVER_SKIPPED (quota met) per pair.  Every
+ * pair is checked as by recover_accumulate before anything is enqueued; on a negative return nothing happened.
+ * Returns SKIPPED if every pair was skipped.  Same bits as n separate calls; for shards so small that the
+ * launch, not HBM, bounds an accumulate. */
+int recover_accumulate_many(recover_ctx *ctx, int n, const int32_t *replicas, const uint32_t *ids,
+                            const void *const *grads, int dtype, int32_t *status_out, void *hip_stream);
+
 /* recover_accumulate followed by recover_snapshot of the same replica and tensor range in ONE pass: the
  * new accumulator value is stored to acc and to snap (Alg. 1 lines 3-5 and 9-10 fused; 4 bytes per element
  * less than the two calls).  Same results, bookkeeping and errors as the two calls; ERR_NO_SNAPSHOT

@@ -23,7 +23,8 @@ MAX_REPLICAS = 64
 
 FUSED_WRITE_GRAD = 1
 
-EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_accumulate_snapshot",
+EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_accumulate_many",
+           "recover_accumulate_snapshot",
            "recover_reduce_adamw_step", "recover_snapshot", "recover_restore",
            "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
            "recover_committed_ids", "recover_last_error", "recover_set_tuning"]
@@ -65,6 +66,8 @@ def lib():
         L.recover_destroy.argtypes = [P]
         L.recover_accumulate.argtypes = [P, I, U32, VP, I, I, I, VP]
         L.recover_accumulate_snapshot.argtypes = [P, I, U32, VP, I, I, I, VP]
+        L.recover_accumulate_many.argtypes = [P, I, C.POINTER(C.c_int32), C.POINTER(U32), C.POINTER(VP), I,
+                                              C.POINTER(C.c_int32), VP]
         L.recover_reduce_adamw_step.argtypes = [P, F, F, F, F, F, U32, VP]
         L.recover_snapshot.argtypes = [P, I, I, I, VP]
         L.recover_restore.argtypes = [P, I, I, VP]
@@ -125,6 +128,17 @@ def recover_destroy(ctx):
 def recover_accumulate(ctx, replica, global_mb_id, grad, dtype, tensor_begin, tensor_end, stream=0):
     return lib().recover_accumulate(ctx, replica, global_mb_id, grad or None, dtype, tensor_begin, tensor_end,
                                     stream or None)
+
+
+def recover_accumulate_many(ctx, replicas, ids, grads, dtype, stream=0):
+    """Returns (code, per-pair status list)."""
+    n = len(replicas)
+    r = (C.c_int32 * n)(*replicas)
+    i = (C.c_uint32 * n)(*ids)
+    g = (C.c_void_p * n)(*[p or None for p in grads])
+    st = (C.c_int32 * n)()
+    code = lib().recover_accumulate_many(ctx, n, r, i, g, dtype, st, stream or None)
+    return code, list(st)
 
 
 def recover_accumulate_snapshot(ctx, replica, global_mb_id, grad, dtype, tensor_begin, tensor_end, stream=0):
@@ -248,6 +262,17 @@ class Shard:
             ptr = g.data_ptr()
         f = recover_accumulate_snapshot if snapshot else recover_accumulate
         return check(f(self.ctx, r, mb_id, ptr, dt, tb, te, self._stream()), self.ctx) == OK
+
+    def accumulate_many(self, replicas, ids, grads):
+        """One launch for several replicas.  Returns the per-pair list of True (accumulated) / False (skipped)."""
+        if self.host_only:
+            ptrs, dt = [0] * len(replicas), F32
+        else:
+            dt = BF16 if grads[0].dtype == self.torch.bfloat16 else F32
+            ptrs = [g.data_ptr() for g in grads]
+        code, st = recover_accumulate_many(self.ctx, list(replicas), list(ids), ptrs, dt, self._stream())
+        check(code, self.ctx)
+        return [x == OK for x in st]
 
     def snapshot(self, r=None, tb=0, te=None):
         te = self.T if te is None else te

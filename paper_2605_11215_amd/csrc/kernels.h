@@ -31,6 +31,14 @@ struct ReduceArgs {
   float divisor;
 };
 
+struct AccumulateManyArgs {
+  float *acc[kMaxReplicas];
+  const void *grad[kMaxReplicas];
+  unsigned char first[kMaxReplicas];  // 1: this replica's first microbatch of the iteration (overwrite)
+};
+hipError_t launch_accumulate_many(const AccumulateManyArgs &a, int n_pairs, bool grad_is_bf16, size_t begin, size_t end,
+                                  hipStream_t s);
+
 // snap != nullptr: the new accumulator value is stored to snap as well (accumulate + snapshot in one pass)
 hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool grad_is_bf16, bool first, size_t begin,
                              size_t end, hipStream_t s);

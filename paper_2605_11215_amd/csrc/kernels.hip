@@ -126,6 +126,30 @@ __global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, float
 }
 
 // ---------------------------------------------------------------------------------------------
+// accumulate for several replicas in one launch (blockIdx.y = pair index): same arithmetic per pair
+// as k_accumulate; for shards so small that the launch, not HBM, bounds a single accumulate.
+// ---------------------------------------------------------------------------------------------
+template <typename G, int T, bool NT>
+__global__ __launch_bounds__(T) void k_accumulate_many(AccumulateManyArgs a, Span sp) {
+  const int pair = blockIdx.y;
+  float *acc = a.acc[pair];
+  const G *g = static_cast<const G *>(a.grad[pair]);
+  const bool first = a.first[pair] != 0;
+  const size_t i = size_t(blockIdx.x) * T + threadIdx.x;
+  if (i < sp.nvec) {
+    f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin) + i;
+    const f32x4 x = load_grad<NT>(g + sp.vbegin, i);
+    f32x4 av = {0.f, 0.f, 0.f, 0.f};
+    if (!first) av = ld<NT>(a4);
+    st<NT>(a4, av + x);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 8) {
+    const size_t e = ragged_index(sp, threadIdx.x);
+    if (e < sp.end) acc[e] = (first ? 0.f : acc[e]) + load_grad1(g, e);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // copy (snapshot and restore): dst[i] = src[i]
 // ---------------------------------------------------------------------------------------------
 template <int T, int U, bool NT>
@@ -466,6 +490,24 @@ hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool gra
     else
       pick(static_cast<const float *>(grad));
   });
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_many(const AccumulateManyArgs &a, int n_pairs, bool grad_is_bf16, size_t begin, size_t end,
+                                  hipStream_t s) {
+  if (begin >= end || n_pairs <= 0) return hipSuccess;
+  const Span sp = make_span(begin, end);
+  const size_t tiles = (sp.nvec + 63) / 64;
+  if (tiles > 0x7FFFFFFFull || n_pairs > kMaxReplicas) return hipErrorInvalidConfiguration;
+  const dim3 grid(tiles ? (unsigned)tiles : 1u, (unsigned)n_pairs);
+  const bool nt = tuning().nontemporal;
+  if (grad_is_bf16) {
+    if (nt) hipLaunchKernelGGL((k_accumulate_many<uint16_t, 64, true>), grid, dim3(64), 0, s, a, sp);
+    else hipLaunchKernelGGL((k_accumulate_many<uint16_t, 64, false>), grid, dim3(64), 0, s, a, sp);
+  } else {
+    if (nt) hipLaunchKernelGGL((k_accumulate_many<float, 64, true>), grid, dim3(64), 0, s, a, sp);
+    else hipLaunchKernelGGL((k_accumulate_many<float, 64, false>), grid, dim3(64), 0, s, a, sp);
+  }
   return hipGetLastError();
 }
 

@@ -316,6 +316,63 @@ int recover_accumulate(recover_ctx *c, int r, uint32_t mb_id, const void *grad, 
   return accumulate_impl(c, r, mb_id, grad, dtype, tb, te, stream, false);
 }
 
+int recover_accumulate_many(recover_ctx *c, int n, const int32_t *replicas, const uint32_t *ids,
+                            const void *const *grads, int dtype, int32_t *status_out, void *stream) {
+  if (!c) return RECOVER_ERR_ARG;
+  if (n < 1 || n > c->W || !replicas || !ids || (!c->host_only && !grads))
+    return fail(c, RECOVER_ERR_ARG, "accumulate_many: bad argument");
+  if (dtype != RECOVER_F32 && dtype != RECOVER_BF16) return fail(c, RECOVER_ERR_ARG, "accumulate_many: dtype %d", dtype);
+  if (c->pending_advance) return fail(c, RECOVER_ERR_STATE, "accumulate_many: policy advancement pending (Alg. 7)");
+  bool seen[kMaxReplicas] = {};
+  for (int i = 0; i < n; ++i) {  // every pair is checked before anything changes
+    const int r = replicas[i];
+    if (r < 0 || r >= c->W || seen[r]) return fail(c, RECOVER_ERR_ARG, "accumulate_many: replica %d out of range or repeated", r);
+    seen[r] = true;
+    if (!c->host_only) {
+      if (!grads[i]) return fail(c, RECOVER_ERR_ARG, "accumulate_many: NULL gradient");
+      if (!aligned16(grads[i])) return fail(c, RECOVER_ERR_ALIGN, "accumulate_many: gradient not 16-byte aligned");
+    }
+    if (!alive(c, r)) return fail(c, RECOVER_ERR_STATE, "accumulate_many: replica %d is dead", r);
+    if (c->contributed[r] >= c->target[r]) continue;
+    if (c->open_mb[r])
+      return fail(c, RECOVER_ERR_STATE, "accumulate_many: microbatch %u of replica %d is incomplete", c->open_id[r], r);
+    if (!c->any_order && !c->ids[r].empty() && ids[i] <= c->ids[r].back())
+      return fail(c, RECOVER_ERR_ARG, "accumulate_many: id %u does not ascend within replica %d", ids[i], r);
+    for (int b = 0; b < c->T; ++b)
+      if (c->cnt[(size_t)r * c->T + b] != c->contributed[r] || c->holds_sum[(size_t)r * c->T + b])
+        return fail(c, RECOVER_ERR_STATE, "accumulate_many: tensor %d of replica %d cannot take this microbatch", b, r);
+  }
+  recover::AccumulateManyArgs a;
+  int m = 0, taken[kMaxReplicas];
+  for (int i = 0; i < n; ++i) {
+    const int r = replicas[i];
+    const bool skip = c->contributed[r] >= c->target[r];
+    if (status_out) status_out[i] = skip ? RECOVER_SKIPPED : RECOVER_OK;
+    if (skip) continue;
+    a.acc[m] = c->acc[r];
+    a.grad[m] = c->host_only ? nullptr : grads[i];
+    a.first[m] = c->contributed[r] == 0;
+    taken[m++] = i;
+  }
+  if (m == 0) return RECOVER_SKIPPED;
+  if (int e = order_after_previous(c, (hipStream_t)stream, "accumulate_many")) return e;
+  if (!c->host_only) {
+    hipError_t he = recover::launch_accumulate_many(a, m, dtype == RECOVER_BF16, 0, (size_t)c->N, (hipStream_t)stream);
+    if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "accumulate_many: %s", hipGetErrorString(he));
+  }
+  for (int j = 0; j < m; ++j) {
+    const int r = replicas[taken[j]];
+    const int k = c->contributed[r];
+    for (int b = 0; b < c->T; ++b) {
+      c->cnt[(size_t)r * c->T + b] = k + 1;
+      c->red_dirty[b] = 1;
+    }
+    c->ids[r].push_back(ids[taken[j]]);
+    c->contributed[r] = k + 1;
+  }
+  return RECOVER_OK;
+}
+
 int recover_accumulate_snapshot(recover_ctx *c, int r, uint32_t mb_id, const void *grad, int dtype, int tb, int te,
                                 void *stream) {
   return accumulate_impl(c, r, mb_id, grad, dtype, tb, te, stream, true);

@@ -18,7 +18,7 @@ def view_oracle(p):
 
 
 def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
-                  snapshot_every=False, hp=HP, on_sync=None, fuse=False):
+                  snapshot_every=False, hp=HP, on_sync=None, fuse=False, batch=False):
     """One iteration of Alg. 1.
 
     dying        {replica: n}: the replica crashes having accumulated n microbatches; the
@@ -27,9 +27,11 @@ def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
                  and all-reduced in place under the old membership (failure case (c), Sec. 4.2)
     fuse         use the engine's one-pass calls where it has them: accumulate+snapshot for
                  snapshot_every, reduce+AdamW for the commit (same results as the separate calls)
+    batch        one accumulate_many call per microbatch slot instead of one accumulate per replica
     Returns dict(decisions=[...], ids={replica: [ids]}).
     """
     fuse = fuse and hasattr(eng, "reduce_adamw_step")
+    batch = batch and hasattr(eng, "accumulate_many") and not (fuse and snapshot_every)
     dying = dict(dying or {})
     crashed = set()
     decisions = []
@@ -38,6 +40,7 @@ def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
         while m < view(eng)["loop_bound"]:
             m += 1
             v = view(eng)
+            pairs = []
             for r in v["alive"]:
                 if r in dying and v["contributed"][r] >= dying[r]:
                     crashed.add(r)
@@ -45,10 +48,14 @@ def run_iteration(eng, view, t, grad_of, W_init, dying=None, fidelity_k=0,
                     continue
                 if v["contributed"][r] < v["target"][r]:
                     mb = r + W_init * v["contributed"][r]
-                    if fuse and snapshot_every:
+                    if batch:
+                        pairs.append((r, mb, grad_of(t, mb)))
+                    elif fuse and snapshot_every:
                         eng.accumulate(r, mb, grad_of(t, mb), snapshot=True)
                     else:
                         eng.accumulate(r, mb, grad_of(t, mb))
+            if pairs:
+                eng.accumulate_many([p[0] for p in pairs], [p[1] for p in pairs], [p[2] for p in pairs])
             if snapshot_every and not fuse:
                 for r in view(eng)["alive"]:
                     if r not in crashed:

@@ -26,7 +26,13 @@ class HipEngine:
     def __getattr__(self, k):
         return getattr(self.s, k)
 
+    def accumulate_many(self, replicas, ids, grads):
+        return self.s.accumulate_many(replicas, ids, [self._device(g) for g in grads])
+
     def accumulate(self, r, mb, g, tb=0, te=None, snapshot=False):
+        return self.s.accumulate(r, mb, self._device(g), tb, te, snapshot=snapshot)
+
+    def _device(self, g):
         torch = self.torch
         if isinstance(g, np.ndarray):
             if self.bf16:
@@ -36,7 +42,7 @@ class HipEngine:
             if h.numel() < 8:
                 h = torch.cat([h, torch.zeros(8, dtype=h.dtype, device=h.device)])
             g = h
-        return self.s.accumulate(r, mb, g, tb, te, snapshot=snapshot)
+        return g
 
 
 def device_grad_source(cfg, buf):

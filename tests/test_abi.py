@@ -137,6 +137,9 @@ def test_protocol_bookkeeping_matches_oracle_call_by_call(static):
             def accumulate(self, r, mb, grad, tb=0, te=None, snapshot=False):
                 return s.accumulate(r, mb, None, tb, te, snapshot=snapshot)
 
+            def accumulate_many(self, replicas, ids, grads):
+                return s.accumulate_many(replicas, ids, None)
+
         h = HostOnly()
         for t in range(5):
             alive = o.world.alive()
@@ -147,7 +150,7 @@ def test_protocol_bookkeeping_matches_oracle_call_by_call(static):
                      for r in rng.choice(alive, nf, replace=False)}
             kw = dict(dying=dying, fidelity_k=int(rng.integers(0, 5)), snapshot_every=bool(rng.integers(0, 2)))
             a = run_iteration(o, view_oracle, t, lambda t, mb: g, W, **kw)
-            b = run_iteration(h, view_hip, t, lambda t, mb: None, W, fuse=bool(trial % 2), **kw)
+            b = run_iteration(h, view_hip, t, lambda t, mb: None, W, fuse=bool(trial % 2), batch=bool(trial % 3 == 0), **kw)
             assert a["ids"] == b["ids"]
             assert len(a["decisions"]) == len(b["decisions"])
             for x, y in zip(a["decisions"], b["decisions"]):
@@ -214,6 +217,12 @@ def test_state_errors_match_the_oracle():
     with pytest.raises(ProtocolError):
         o2.restore(0, stale_only=False)
     assert B.recover_restore(s2.ctx, 0, 0) == B.ERR_STATE
-    # no snapshot buffers
-    code, ctx = B.recover_init(2, 2, [0, 8], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)
-    assert code == 0
+    # accumulate_many: a bad pair leaves everything untouched; a met quota is skipped per pair
+    s3 = B.Shard(4, 1, off, host_only=True)
+    assert s3.accumulate(2, 2, None)
+    assert B.recover_accumulate_many(s3.ctx, [0, 0], [0, 4], [0, 0], B.F32)[0] == B.ERR_ARG      # repeated replica
+    assert B.recover_accumulate_many(s3.ctx, [0, 9], [0, 4], [0, 0], B.F32)[0] == B.ERR_ARG
+    assert s3.query()["contributed"] == [0, 0, 1, 0]
+    assert s3.accumulate_many([0, 1, 2], [0, 1, 6], None) == [True, True, False]
+    assert s3.query()["contributed"] == [1, 1, 1, 0]
+    assert B.recover_accumulate_many(s3.ctx, [0, 1], [4, 5], [0, 0], B.F32)[0] == B.SKIPPED

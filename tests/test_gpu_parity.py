@@ -324,3 +324,21 @@ def test_fused_calls_give_the_bits_of_the_separate_calls(bf16):
             pass
     s_f.reduce_adamw_step(**hp32())
     assert float(s_f.grad_out.min()) == 7.0 == float(s_f.grad_out.max())
+
+
+def test_accumulate_many_gives_the_bits_of_separate_calls():
+    torch = torch_()
+    N = OFF[-1]
+    for bf16 in (False, True):
+        g = grads_np(29, N, 1e-3, bf16)
+        o32, s_b, eng_b = make_pair(8, 2, OFF, bf16, seed=29)
+        _, s_u, eng_u = make_pair(8, 2, OFF, bf16, seed=29)
+        for t, kw in enumerate([dict(), dict(dying={2: 1, 5: 0}, fidelity_k=3), dict()]):
+            before = state_of(s_b, N)
+            a = run_iteration(o32, view_oracle, t, g, 8, hp=hp32(), **kw)
+            b = run_iteration(eng_b, view_hip, t, g, 8, hp=hp32(), batch=True, fuse=True, **kw)
+            c = run_iteration(eng_u, view_hip, t, g, 8, hp=hp32(), **kw)
+            assert a["ids"] == b["ids"] == c["ids"]
+            for x, y in [(s_b.grad_out, s_u.grad_out), (s_b.param, s_u.param), (s_b.exp_avg_sq, s_u.exp_avg_sq)]:
+                assert torch.equal(x, y)
+            compare_iteration(o32, s_b, N, before)
