@@ -245,6 +245,37 @@ def main():
         batched = dict(ms_per_step=dtb * 1e3, launches=G + 1, bytes_per_elem=b_fused, GBps=b_fused * N / dtb / 1e9,
                        microbatches_per_s=M / dtb)
 
+    # Non-blocking restoration (Alg. 5): rewind every replica from its snapshot while the main stream
+    # generates the next microbatch's gradient (the stand-in for the extended pass's forward/backward),
+    # then re-reduce.  Serial = all on one stream; overlapped = the rewind on a side stream, ordered by
+    # the context's events.
+    def restore_then_reduce(side):
+        e0, e1 = ev(), ev()
+        e0.record()
+        if side is None:
+            assert B.recover_restore(ctx, -1, 0, stream) == 0
+        else:
+            assert B.recover_restore(ctx, -1, 0, side.cuda_stream) == 0
+        synth.fill_device(pool[0], c["seed"], S.TAG_GRAD, 99, 0, c["scale"], c["kind"])
+        assert B.recover_reduce(ctx, 0, T, 0, stream) == 0
+        e1.record()
+        return e0, e1
+
+    for k in range(G):
+        for r in range(W):
+            assert B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream) == 0
+    assert B.recover_snapshot(ctx, -1, 0, T, stream) == 0
+    side = torch.cuda.Stream()
+    pairs = {"serial": [], "overlapped": []}
+    for i in range(12):
+        for name, sd in (("serial", None), ("overlapped", side)):
+            pairs[name].append(restore_then_reduce(sd))
+    torch.cuda.synchronize()
+    restore_overlap = {k: sum(a_.elapsed_time(b_) for a_, b_ in v[2:]) / len(v[2:]) for k, v in pairs.items()}
+    restore_overlap = dict(serial_ms=restore_overlap["serial"], overlapped_ms=restore_overlap["overlapped"],
+                           what="restore of %d replicas + generation of one gradient + reduce" % W)
+    assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], stream) == 0
+
     out = {
         "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
@@ -260,6 +291,7 @@ def main():
         "fused_reduce_adamw": fused,
         "fused_snapshot_every_microbatch": every,
         "batched_launches": batched,
+        "nonblocking_restore": restore_overlap,
         "roofline": {"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % ("bf16" if c["bf16"] else "float"), "achieved": k_gbs["accumulate_rmw"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
                      "traffic": read_traffic() if a.workload == 2 else None, "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,

@@ -342,3 +342,39 @@ def test_accumulate_many_gives_the_bits_of_separate_calls():
             for x, y in [(s_b.grad_out, s_u.grad_out), (s_b.param, s_u.param), (s_b.exp_avg_sq, s_u.exp_avg_sq)]:
                 assert torch.equal(x, y)
             compare_iteration(o32, s_b, N, before)
+
+
+def test_degenerate_shapes_and_special_values():
+    """Empty shard, one replica, one microbatch; infinities, NaNs and subnormal numbers go through the
+    adds and the divide as IEEE arithmetic says (the oracle is NumPy on the CPU)."""
+    torch = torch_()
+    # an empty shard: every call is a no-op that still keeps the books
+    s = B.Shard(2, 1, [0, 0])
+    z = torch.zeros(8, device="cuda")
+    assert s.accumulate(0, 0, z) and s.accumulate(1, 1, z)
+    s.snapshot()
+    s.reduce()
+    s.adamw_step(**hp32())
+    s.advance()
+    # W = 1, G = 1 with special values
+    vals = np.array([np.inf, -np.inf, np.nan, 1e-40, -1e-45, 3e-39, 1.0, -0.0, 2e-38, 1.17549435e-38, 0.0, 5e-41, 7.0],
+                    np.float32)
+    off = [0, len(vals)]
+    for W, G in ((1, 1), (2, 2), (3, 1)):
+        o = Proto(W, G, off, dtype=np.float32)
+        o.set_state(np.zeros(len(vals), np.float32))
+        s = B.Shard(W, G, off)
+        eng = HipEngine(s)
+        with np.errstate(all="ignore"):
+            for k in range(G):
+                for r in range(W):
+                    gk = (vals * np.float32(1 + r + k)).astype(np.float32)
+                    o.accumulate(r, r + W * k, gk)
+                    eng.accumulate(r, r + W * k, gk)
+            o.reduce()
+            s.reduce()
+        got = s.grad_out[:len(vals)].cpu().numpy()
+        assert np.array_equal(np.isnan(got), np.isnan(o.grad_out))
+        ok = ~np.isnan(got)
+        assert bits_equal(got[ok], o.grad_out[ok]), (W, G, got, o.grad_out)
+        assert got[3] != 0 and got[4] != 0                      # subnormals are kept, not flushed
