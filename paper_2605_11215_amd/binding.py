@@ -60,6 +60,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("librecover.so is not built; run `python -m paper_2605_11215_amd.build` "
                                "(there is no CPU implementation of this library)")
+        # PyTorch ships its own HIP runtime; it has to be in the process first so that this library
+        # binds to the same runtime instead of loading a second one (device pointers and streams
+        # are shared between the two).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         P, I, U32, F, VP = C.c_void_p, C.c_int, C.c_uint32, C.c_float, C.c_void_p
         L.recover_init.argtypes = [C.POINTER(Config), C.POINTER(P)]

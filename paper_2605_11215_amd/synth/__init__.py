@@ -19,6 +19,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libsynth.so is not built; run `python -m paper_2605_11215_amd.build`")
+        # PyTorch ships its own HIP runtime; it has to be in the process first so that this library
+        # binds to the same runtime instead of loading a second one (device pointers and streams
+        # are shared between the two).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.synth_fill.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
                                  C.c_uint32, C.c_double, C.c_int, C.c_void_p]
