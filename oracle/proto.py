@@ -120,12 +120,14 @@ class Proto:
     def snapshot(self, r=None, tb=0, te=None):
         w = self.world
         tb, te = self._rng(tb, te)
-        for q in (w.alive() if r is None else [r]):
+        who = w.alive() if r is None else [r]
+        for q in who:
             if w.role[q] == DEAD:
                 raise ProtocolError("dead replica")
+            if any(self.inplace_sum[q][b] for b in range(tb, te)):
+                raise ProtocolError("bucket already holds a reduced sum")
+        for q in who:
             for b in range(tb, te):
-                if self.inplace_sum[q][b]:
-                    raise ProtocolError("bucket already holds a reduced sum")
                 lo, hi = self.off[b], self.off[b + 1]
                 self.snap[q][lo:hi] = self.acc[q][lo:hi]
                 self.snap_valid[q][b] = True
@@ -142,10 +144,13 @@ class Proto:
             return False
         divisor = w.B if w.static else sum(w.contributed[r] for r in w.contributors())
         for b in range(tb, te):
-            lo, hi = self.off[b], self.off[b + 1]
-            members = [r for r in w.contributors() if self.cnt[r][b] > 0]
             if any(self.inplace_sum[r][b] for r in w.alive()):
                 raise ProtocolError("bucket %d was already reduced in place" % b)
+        if divisor <= 0:
+            raise ProtocolError("nothing has been contributed")
+        for b in range(tb, te):
+            lo, hi = self.off[b], self.off[b + 1]
+            members = [r for r in w.contributors() if self.cnt[r][b] > 0]
             total = np.zeros(hi - lo, self.dtype)
             first = True
             for r in members:

@@ -226,3 +226,30 @@ def test_state_errors_match_the_oracle():
     assert s3.accumulate_many([0, 1, 2], [0, 1, 6], None) == [True, True, False]
     assert s3.query()["contributed"] == [1, 1, 1, 0]
     assert B.recover_accumulate_many(s3.ctx, [0, 1], [4, 5], [0, 0], B.F32)[0] == B.SKIPPED
+
+
+def test_random_call_sequences_agree_with_the_oracle_host_only():
+    """Differential test of the host logic: thousands of random calls (valid and invalid) leave the
+    library's bookkeeping equal to the oracle's after every call."""
+    from tests import differential
+
+    class HostOnly:
+        def __init__(self, s):
+            self.s = s
+
+        def __getattr__(self, k):
+            return getattr(self.s, k)
+
+        def accumulate(self, r, mb, g, tb=0, te=None, snapshot=False):
+            return self.s.accumulate(r, mb, None, tb, te, snapshot=snapshot)
+
+    total = {"ok": 0, "err": 0, "steps": 0, "failures": 0}
+    for seed in range(40):
+        W, G = [(4, 2), (8, 1), (3, 3), (6, 2), (2, 4)][seed % 5]
+        off = [0, 3, 8, 8, 20]
+        s = B.Shard(W, G, off, host_only=True, flags=B.FLAG_ADAPTIVE if seed % 8 == 7 else 0)
+        st = differential.run(seed, 400, W, G, off, HostOnly(s), adaptive=(seed % 8 == 7))
+        for k in total:
+            total[k] += st[k]
+        s.close()
+    assert total["ok"] > 8000 and total["err"] > 500 and total["steps"] > 200 and total["failures"] > 40, total

@@ -378,3 +378,43 @@ def test_degenerate_shapes_and_special_values():
         ok = ~np.isnan(got)
         assert bits_equal(got[ok], o.grad_out[ok]), (W, G, got, o.grad_out)
         assert got[3] != 0 and got[4] != 0                      # subnormals are kept, not flushed
+
+
+def test_random_call_sequences_agree_with_the_oracle_on_the_gpu():
+    """The differential test with real buffers: after random calls (partial tensor ranges, partial
+    microbatches, snapshots, in-place reductions, failures, rewinds, steps) the accumulators of
+    every live replica, the snapshots, the gradient and the AdamW state equal the fp32 oracle's."""
+    torch = torch_()
+    from tests import differential
+    off = [0, 3, 8, 8, 4107, 4200]
+    N = off[-1]
+    total = {"ok": 0, "err": 0, "steps": 0, "failures": 0}
+    for seed in range(6):
+        W, G = [(4, 2), (8, 1), (3, 3)][seed % 3]
+        s = B.Shard(W, G, off)
+        eng = HipEngine(s)
+        pool = [S.fill(N, 31 + seed, S.TAG_GRAD, j, 0, 1e-3) for j in range(16)]
+
+        def compare(o, lib, where):
+            for r in o.world.alive():
+                a = s.acc[r][:N].cpu().numpy()
+                sn = s.snap[r][:N].cpu().numpy()
+                for b in range(len(off) - 1):
+                    lo, hi = off[b], off[b + 1]
+                    if o.cnt[r][b] > 0 or o.inplace_sum[r][b]:
+                        assert bits_equal(a[lo:hi], o.acc[r][lo:hi]), (where, "acc", r, b)
+                    if o.snap_valid[r][b] and o.snap_cnt[r][b] > 0:
+                        assert bits_equal(sn[lo:hi], o.snap[r][lo:hi]), (where, "snap", r, b)
+            g = s.grad_out[:N].cpu().numpy()
+            for b in range(len(off) - 1):
+                if o.red_eps[b] >= 0:
+                    assert bits_equal(g[off[b]:off[b + 1]], o.grad_out[off[b]:off[b + 1]]), (where, "grad", b)
+            if o.t > 0:
+                assert max_rel(s.param[:N].cpu().numpy(), o.param) <= 1e-6 or not np.any(o.param), where
+                assert max_rel(s.exp_avg_sq[:N].cpu().numpy(), o.v) <= 1e-6, where
+
+        st = differential.run(100 + seed, 250, W, G, off, eng, grads=lambda i: pool[i % 16], compare_buffers=compare)
+        for k in total:
+            total[k] += st[k]
+        s.close()
+    assert total["steps"] > 20 and total["failures"] > 5, total
