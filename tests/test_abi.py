@@ -253,3 +253,41 @@ def test_random_call_sequences_agree_with_the_oracle_host_only():
             total[k] += st[k]
         s.close()
     assert total["ok"] > 8000 and total["err"] > 500 and total["steps"] > 200 and total["failures"] > 40, total
+
+
+def test_stale_reduction_and_rewound_audit_in_the_library():
+    """The library refuses to commit a reduction from before a repair even when the totals are B, and a
+    rewind drops completed microbatches from its audit (same scenarios as the oracle's pins)."""
+    s = B.Shard(6, 2, [0, 2, 4], host_only=True)
+    for k in range(2):
+        for r in range(6):
+            if not (r == 5 and k == 1):
+                assert s.accumulate(r, r + 6 * k, None)
+    d = s.on_failure([5])
+    s.restore()
+    assert d["at_boundary"] and d["G_ext"] == 1 and d["n_bdry"] == 3
+    for r in range(5):
+        while s.accumulate(r, 100 + r + 6 * s.query()["contributed"][r], None):
+            pass
+    s.reduce()
+    s.adamw_step(**HP)
+    assert s.advance()["role"] == [0, 0, 0, 0, 2, 4]
+    for k in range(3):
+        for r in range(5):
+            assert s.accumulate(r, r + 6 * k, None)
+    s.reduce()
+    d = s.on_failure([1])
+    assert not d["at_boundary"] and d["role"][4] == B.ROLE_MAJOR and d["C_cur"] == 12
+    s.restore()
+    assert B.recover_adamw_step(s.ctx, 1e-3, 0.9, 0.95, 1e-8, 0.1) == B.ERR_STATE
+    s.reduce()
+    s.adamw_step(**HP)
+    # rewind drops a completed microbatch
+    s2 = B.Shard(2, 3, [0, 4, 8], host_only=True)
+    s2.accumulate(0, 0, None)
+    s2.snapshot(0)
+    s2.accumulate(0, 2, None)
+    assert B.recover_committed_ids(s2.ctx, 0)[1] == [0, 2]
+    s2.restore(0, stale_only=False)
+    assert B.recover_committed_ids(s2.ctx, 0)[1] == [0] and s2.query()["contributed"][0] == 1
+    assert s2.accumulate(0, 2, None)

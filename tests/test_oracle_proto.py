@@ -123,6 +123,22 @@ def test_promoted_spare_contributes_its_own_microbatches_after_rewind():
     assert terms_of(total[0]) == [0, 2, 3, 4, 6, 8, 9, 10, 12, 14, 15, 16]
 
 
+def test_spare_is_masked_out_of_the_sum():
+    """Sec. 4.3: a spare runs the same microbatches as its counterpart but does not enter the global
+    batch.  Six replicas, one lost: four majors at 3 and one major-spare; the next, failure-free
+    iteration commits the majors' twelve ids and none of the spare's (4, 10, 16)."""
+    off = [0, 2, 4]
+    p = new_proto(6, 2, off=off)
+    run_iteration(p, view_oracle, 0, coded(4), 6, dying={5: 2})
+    assert p.world.role == [0, 0, 0, 0, 2, 4]
+    out = run_iteration(p, view_oracle, 1, coded(4), 6)
+    total = p.grad_out * 12
+    assert np.all(total == total[0])
+    assert terms_of(total[0]) == [0, 1, 2, 3, 6, 7, 8, 9, 12, 13, 14, 15]
+    assert p.ids[4] == [] and 4 not in out["ids"]            # the iteration is over; the spare never counted
+    assert len(p.world.alive()) == 5
+
+
 def test_constant_gradient_closed_form_and_constant_divisor():
     """If every microbatch gradient equals c the committed mean is c whatever failed: the
     divisor stays B = W_init * G_init (Sec. 4.3, Eq. 1; implementation appendix)."""
@@ -241,3 +257,62 @@ def test_protocol_violations_are_errors():
         p.accumulate(1, 99, g(0, 0))                   # dead replica
     with pytest.raises(ProtocolError):
         p.accumulate(0, 2, g(0, 0))                    # ids must ascend within a replica
+
+
+def test_rewind_drops_completed_microbatches_from_the_audit():
+    """A snapshot at a microbatch boundary, one more complete microbatch, then a rewind of the
+    whole replica: count, audit and committed set are those of the boundary, and the same
+    microbatch can be accumulated again (Sec. 4.2: rewound work is as if never done)."""
+    g = grads(11)
+    p = new_proto(2, 3, dtype=np.float32)
+    p.accumulate(0, 0, g(0, 0))
+    p.snapshot(0)
+    at_boundary = p.acc[0].copy()
+    p.accumulate(0, 2, g(0, 2))
+    assert p.ids[0] == [0, 2] and p.world.contributed[0] == 2
+    p.restore(0, stale_only=False)
+    assert p.ids[0] == [0] and p.world.contributed[0] == 1 and p.cnt[0] == [1] * p.T
+    assert np.array_equal(p.acc[0], at_boundary)
+    assert p.accumulate(0, 2, g(0, 2)) and p.ids[0] == [0, 2]
+
+
+def test_inplace_reduction_leaves_the_sum_in_every_survivor():
+    """Alg. 2 Reduce is an in-place all-reduce: afterwards every member of the group, spares
+    included, holds the sum; a spare's own gradients come back only through the rewind."""
+    off = [0, 2, 4]
+    p = new_proto(6, 2, off=off)
+    run_iteration(p, view_oracle, 0, coded(4), 6, dying={5: 2})       # leaves r4 a major-spare
+    for k in range(3):
+        for r in range(5):
+            p.accumulate(r, r + 6 * k, coded(4)(1, r + 6 * k))
+    own = p.acc[4].copy()
+    p.snapshot(None)
+    p.reduce(0, 1, inplace=True)
+    want = sum(2.0 ** j for j in (0, 1, 2, 3, 6, 7, 8, 9, 12, 13, 14, 15))
+    for r in range(5):
+        assert np.all(p.acc[r][0:2] == want), r                       # the spare's bucket too
+        assert np.array_equal(p.acc[r][2:4], (own if r == 4 else p.acc[r])[2:4])
+    p.restore(4, stale_only=False)
+    assert np.array_equal(p.acc[4], own)
+
+
+def test_reduction_under_an_older_epoch_cannot_be_committed():
+    """Sec. 4.2: everything admitted must be reduced under one membership.  A failure absorbed by a
+    spare leaves the totals at B, yet a reduction from before the repair holds the dead replica's
+    gradients and lacks the promoted spare's: the step is refused until it is redone."""
+    off = [0, 2, 4]
+    p = new_proto(6, 2, off=off)
+    run_iteration(p, view_oracle, 0, coded(4), 6, dying={5: 2})       # r4 becomes a major-spare
+    for k in range(3):
+        for r in range(5):
+            p.accumulate(r, r + 6 * k, coded(4)(1, r + 6 * k))
+    p.reduce()                                                        # no snapshots taken
+    d = p.on_failure([1])
+    assert not d["at_boundary"] and d["role"][4] == 0
+    p.restore(None)                                                   # nothing to rewind
+    assert p.world.C_cur() == 12
+    with pytest.raises(ProtocolError):
+        p.adamw_step(**HP)
+    p.reduce()
+    assert terms_of((p.grad_out * 12)[0]) == [0, 2, 3, 4, 6, 8, 9, 10, 12, 14, 15, 16]
+    p.adamw_step(**HP)
