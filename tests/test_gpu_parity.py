@@ -418,3 +418,44 @@ def test_random_call_sequences_agree_with_the_oracle_on_the_gpu():
             total[k] += st[k]
         s.close()
     assert total["steps"] > 20 and total["failures"] > 5, total
+
+
+def test_bucketed_arrival_in_reverse_order_with_failure_during_the_bucket_loop():
+    """The paper's bucket loop (Alg. 1 lines 8-14, walk-through appendix): gradients arrive bucket by
+    bucket in reverse order, each bucket is snapshotted and all-reduced in place as soon as the last
+    microbatch has produced it; a replica fails after some buckets were reduced.  300 tensors of
+    0..40 elements in 13 buckets: every bucket boundary is ragged."""
+    rng = np.random.default_rng(3)
+    off = [0] + [int(x) for x in np.cumsum(rng.integers(0, 41, 300))]
+    N, T = off[-1], 300
+    cuts = sorted(set([0, T] + [int(x) for x in rng.integers(1, T, 12)]))
+    buckets = list(zip(cuts[:-1], cuts[1:]))[::-1]
+    W, G = 4, 2
+    o, s, eng = make_pair(W, G, off, False, seed=37)
+    g = grads_np(37, N, 1e-3, False)
+    before = state_of(s, N)
+    for e in (o, eng):
+        def feed(r):
+            k = (view_oracle(e) if e is o else view_hip(s))["contributed"][r]
+            mb = r + W * k
+            for tb, te in buckets:
+                e.accumulate(r, mb, g(0, mb), tb, te)
+        for k in range(G):
+            for r in range(W):
+                if not (r == 2 and k == 1):                  # replica 2 crashes after one microbatch
+                    feed(r)
+        for tb, te in buckets[:5]:                           # five buckets go through before the failure shows
+            e.snapshot(None, tb, te)
+            e.reduce(tb, te, inplace=True)
+        d = e.on_failure([2])
+        assert d["at_boundary"] and d["G_ext"] == 1 and d["n_bdry"] == 1
+        e.restore(None, stale_only=True)
+        for r in (0, 1):                                     # the extended pass (replica 3 is the boundary minor)
+            feed(r)
+        for tb, te in buckets:
+            e.snapshot(None, tb, te)
+            e.reduce(tb, te, inplace=True)
+        e.adamw_step(**hp32())
+        e.advance()
+    compare_iteration(o, s, N, before)
+    assert view_hip(s)["target"] == list(o.world.target)
