@@ -205,6 +205,21 @@ int recover_query(recover_ctx *ctx, recover_decision *out);
  * Writes min(count, cap) ids and returns the count, or a negative code. */
 int recover_committed_ids(recover_ctx *ctx, int replica, uint32_t *ids_out, int cap);
 
+/* Verification support (not a step of the path): compares two device fp32 buffers of n elements on the GPU.
+ * The 40-byte result is written to DEVICE memory `out_device` (caller-owned, 8-byte aligned), asynchronously on
+ * the stream; the caller copies it back.  max_abs_diff and max_abs_ref skip NaNs; the checksums are
+ * sum(bits[i] * (2 i + 1)) mod 2^64, so equal checksums of x and ref with n_mismatch == 0 mean equal buffers.
+ * The result does not depend on the launch shape. */
+typedef struct {
+  uint64_t n_mismatch;   /* elements whose bit patterns differ */
+  uint64_t n_nan;        /* elements where x or ref is a NaN */
+  uint64_t checksum_x;
+  uint64_t checksum_ref;
+  float max_abs_diff;    /* max |x[i] - ref[i]| */
+  float max_abs_ref;     /* max |ref[i]| */
+} recover_compare_result;
+int recover_compare(const float *x, const float *ref, int64_t n, recover_compare_result *out_device, void *hip_stream);
+
 /* Message of the last negative return on this context (or of recover_init if ctx == NULL). */
 const char *recover_last_error(const recover_ctx *ctx);
 

@@ -27,7 +27,7 @@ EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_acc
            "recover_accumulate_snapshot",
            "recover_reduce_adamw_step", "recover_snapshot", "recover_restore",
            "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
-           "recover_committed_ids", "recover_last_error", "recover_set_tuning"]
+           "recover_committed_ids", "recover_compare", "recover_last_error", "recover_set_tuning"]
 
 
 class RecoverError(RuntimeError):
@@ -80,6 +80,7 @@ def lib():
         L.recover_adamw_step.argtypes = [P, F, F, F, F, F, VP]
         L.recover_query.argtypes = [P, C.POINTER(Decision)]
         L.recover_committed_ids.argtypes = [P, I, C.POINTER(U32), I]
+        L.recover_compare.argtypes = [VP, VP, C.c_int64, VP, VP]
         L.recover_last_error.argtypes = [P]
         L.recover_last_error.restype = C.c_char_p
         L.recover_set_tuning.argtypes = [I, I]
@@ -202,6 +203,26 @@ def recover_committed_ids(ctx, replica, cap=4096):
     buf = (C.c_uint32 * cap)()
     n = lib().recover_committed_ids(ctx, replica, buf, cap)
     return n, list(buf[:max(0, min(n, cap))])
+
+
+class CompareResult(C.Structure):
+    _fields_ = [("n_mismatch", C.c_uint64), ("n_nan", C.c_uint64), ("checksum_x", C.c_uint64),
+                ("checksum_ref", C.c_uint64), ("max_abs_diff", C.c_float), ("max_abs_ref", C.c_float)]
+
+
+def recover_compare(x, ref, n, out_device, stream=0):
+    return lib().recover_compare(x, ref, n, out_device, stream or None)
+
+
+def compare_tensors(x, ref, n=None):
+    """Compare two float32 device tensors on the GPU through recover_compare; returns a dict."""
+    import torch
+    n = min(x.numel(), ref.numel()) if n is None else n
+    out = torch.empty(5, dtype=torch.int64, device=x.device)
+    check(recover_compare(x.data_ptr(), ref.data_ptr(), n, out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    raw = out.cpu().numpy().tobytes()
+    r = CompareResult.from_buffer_copy(raw)
+    return {k: getattr(r, k) for k, _ in CompareResult._fields_}
 
 
 def recover_set_tuning(key, value):

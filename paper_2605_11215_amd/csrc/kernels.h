@@ -31,6 +31,14 @@ struct ReduceArgs {
   float divisor;
 };
 
+// Device-side layout of recover_compare_result (include/recover.h); the two maxima are kept as the bit
+// patterns of non-negative floats.
+struct CompareResult {
+  uint64_t n_mismatch, n_nan, checksum_x, checksum_ref;
+  uint32_t max_abs_diff_bits, max_abs_ref_bits;
+};
+hipError_t launch_compare(const float *x, const float *ref, size_t n, CompareResult *out, hipStream_t s);
+
 struct AccumulateManyArgs {
   float *acc[kMaxReplicas];
   const void *grad[kMaxReplicas];

@@ -420,6 +420,69 @@ __global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, float *__restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// compare (verification support, off the timed path): bitwise mismatch count, max |x - ref|,
+// max |ref|, NaN count and two position-weighted 64-bit checksums of two fp32 buffers, without
+// moving them to the host.  Each lane folds its elements, a wavefront folds its 64 lanes with
+// cross-lane shuffles, one lane per wavefront adds to the result with integer atomics (sums and
+// maxima of integers do not depend on the order, so the result is reproducible).
+// ---------------------------------------------------------------------------------------------
+__device__ inline uint64_t wave_sum_u64(uint64_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+__device__ inline uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)v, d, 64);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(256) void k_compare_clear(CompareResult *out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    out->n_mismatch = out->n_nan = out->checksum_x = out->checksum_ref = 0;
+    out->max_abs_diff_bits = out->max_abs_ref_bits = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, const float *__restrict__ ref, size_t n,
+                                                 CompareResult *out) {
+  uint64_t mism = 0, nans = 0, cx = 0, cr = 0;
+  uint32_t mdiff = 0, mref = 0;  // bit patterns of non-negative floats order like the floats
+  for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += size_t(gridDim.x) * 256) {
+    const float a = x[i], b = ref[i];
+    const uint32_t ab = __builtin_bit_cast(uint32_t, a), bb = __builtin_bit_cast(uint32_t, b);
+    mism += ab != bb;
+    cx += uint64_t(ab) * (2 * uint64_t(i) + 1);
+    cr += uint64_t(bb) * (2 * uint64_t(i) + 1);
+    if (a != a || b != b) {
+      nans += 1;
+    } else {
+      const uint32_t d = __builtin_bit_cast(uint32_t, __builtin_fabsf(a - b));
+      const uint32_t r = bb & 0x7FFFFFFFu;
+      mdiff = d > mdiff ? d : mdiff;
+      mref = r > mref ? r : mref;
+    }
+  }
+  mism = wave_sum_u64(mism);
+  nans = wave_sum_u64(nans);
+  cx = wave_sum_u64(cx);
+  cr = wave_sum_u64(cr);
+  mdiff = wave_max_u32(mdiff);
+  mref = wave_max_u32(mref);
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_mismatch), (unsigned long long)mism);
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_nan), (unsigned long long)nans);
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->checksum_x), (unsigned long long)cx);
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->checksum_ref), (unsigned long long)cr);
+    atomicMax(&out->max_abs_diff_bits, mdiff);
+    atomicMax(&out->max_abs_ref_bits, mref);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
 static bool grid_for(size_t nvec, int T, int U, unsigned *grid, size_t *ntiles) {
@@ -589,6 +652,16 @@ hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v
   };
   if (tuning().nontemporal) with_wg(std::true_type{});
   else with_wg(std::false_type{});
+  return hipGetLastError();
+}
+
+hipError_t launch_compare(const float *x, const float *ref, size_t n, CompareResult *out, hipStream_t s) {
+  hipLaunchKernelGGL(k_compare_clear, dim3(1), dim3(256), 0, s, out);
+  if (n > 0) {
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(k_compare, dim3((unsigned)blocks), dim3(256), 0, s, x, ref, n, out);
+  }
   return hipGetLastError();
 }
 

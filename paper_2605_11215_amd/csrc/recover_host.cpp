@@ -774,6 +774,16 @@ int recover_committed_ids(recover_ctx *c, int r, uint32_t *ids_out, int cap) {
   return n;
 }
 
+int recover_compare(const float *x, const float *ref, int64_t n, recover_compare_result *out_device, void *stream) {
+  static_assert(sizeof(recover_compare_result) == sizeof(recover::CompareResult), "result layouts must agree");
+  if (!x || !ref || !out_device || n < 0) return fail(nullptr, RECOVER_ERR_ARG, "compare: bad argument");
+  if ((reinterpret_cast<uintptr_t>(out_device) & 7u) != 0) return fail(nullptr, RECOVER_ERR_ALIGN, "compare: result not 8-byte aligned");
+  hipError_t he = recover::launch_compare(x, ref, (size_t)n, reinterpret_cast<recover::CompareResult *>(out_device),
+                                          (hipStream_t)stream);
+  if (he != hipSuccess) return fail(nullptr, RECOVER_ERR_HIP, "compare: %s", hipGetErrorString(he));
+  return RECOVER_OK;
+}
+
 int recover_set_tuning(int key, int value) {
   recover::Tuning &t = recover::tuning();
   switch (key) {

@@ -459,3 +459,27 @@ def test_bucketed_arrival_in_reverse_order_with_failure_during_the_bucket_loop()
         e.advance()
     compare_iteration(o, s, N, before)
     assert view_hip(s)["target"] == list(o.world.target)
+
+
+def test_device_compare_matches_numpy():
+    torch = torch_()
+    rng = np.random.default_rng(41)
+    for n in (0, 1, 63, 64, 1000003):
+        x = rng.normal(0, 1, max(n, 1)).astype(np.float32)[:n]
+        y = x.copy()
+        if n > 10:
+            y[[3, n // 2, n - 1]] += np.float32(0.5)
+            y[7] = np.nan
+            x[9] = -0.0
+            y[9] = 0.0                                            # equal as numbers, different bits
+        got = B.compare_tensors(torch.from_numpy(np.append(x, 0).astype(np.float32)).cuda(),
+                                torch.from_numpy(np.append(y, 0).astype(np.float32)).cuda(), n)
+        xb, yb = x.view(np.uint32).astype(np.uint64), y.view(np.uint32).astype(np.uint64)
+        w = 2 * np.arange(n, dtype=np.uint64) + np.uint64(1)
+        assert got["n_mismatch"] == int(np.sum(xb != yb))
+        assert got["n_nan"] == int(np.sum(np.isnan(x) | np.isnan(y)))
+        assert got["checksum_x"] == int(np.sum(xb * w, dtype=np.uint64))
+        assert got["checksum_ref"] == int(np.sum(yb * w, dtype=np.uint64))
+        ok = ~(np.isnan(x) | np.isnan(y))
+        assert got["max_abs_diff"] == (np.max(np.abs(x[ok] - y[ok])) if ok.any() else 0.0)
+        assert got["max_abs_ref"] == (np.max(np.abs(y[ok])) if ok.any() else 0.0)
