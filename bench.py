@@ -244,6 +244,29 @@ def main():
         dtb = (time.perf_counter() - t2) / a.steps
         batched = dict(ms_per_step=dtb * 1e3, launches=G + 1, bytes_per_elem=b_fused, GBps=b_fused * N / dtb / 1e9,
                        microbatches_per_s=M / dtb)
+        # the same iteration captured once into a HIP graph (step count on the device) and replayed
+        sg = B.Shard(W, G, off, device="cuda:0", snapshots=False, device_step=True)
+        synth.fill_device(sg.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=N)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cs = torch.cuda.current_stream().cuda_stream
+            for k in range(G):
+                rc, _ = B.recover_accumulate_many(sg.ctx, list(range(W)), [r + W * k for r in range(W)],
+                                                  [gptr[(k * W + r) % POOL] for r in range(W)], gcode, cs)
+                assert rc == 0, rc
+            assert B.recover_reduce_adamw_step(sg.ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"],
+                                               HP["weight_decay"], 0, cs) == 0
+            assert B.recover_policy_adjust(sg.ctx, [], W)[0] == 0
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(a.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dtg = (time.perf_counter() - t3) / a.steps
+        batched["graph_replay"] = dict(ms_per_step=dtg * 1e3, GBps=b_fused * N / dtg / 1e9, microbatches_per_s=M / dtg)
 
     # Non-blocking restoration (Alg. 5): rewind every replica from its snapshot while the main stream
     # generates the next microbatch's gradient (the stand-in for the extended pass's forward/backward),

@@ -99,6 +99,11 @@ typedef struct {
   float *exp_avg_sq;             /* device, n_elems floats: AdamW second moment */
   uint16_t *param_bf16;          /* device, n_elems bf16 or NULL: rounded copy of param after each step */
   uint32_t flags;
+  void *step_state;              /* device, 64 bytes, zero-filled by the caller before the first step, or NULL.
+                                    If given, the optimiser's step count and bias-correction products live
+                                    there and advance on the device (a one-thread kernel before each update),
+                                    so that a HIP graph captured around an iteration stays correct when it is
+                                    replayed; the results are the same bits as without it. */
 } recover_config;
 
 #define RECOVER_MAX_REPLICAS 64

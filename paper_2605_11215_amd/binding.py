@@ -41,7 +41,7 @@ class Config(C.Structure):
                 ("tensor_offsets", C.POINTER(C.c_int64)), ("acc", C.POINTER(C.c_void_p)),
                 ("snap", C.POINTER(C.c_void_p)), ("grad_out", C.c_void_p), ("param", C.c_void_p),
                 ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p), ("param_bf16", C.c_void_p),
-                ("flags", C.c_uint32)]
+                ("flags", C.c_uint32), ("step_state", C.c_void_p)]
 
 
 class Decision(C.Structure):
@@ -102,7 +102,7 @@ def check(code, ctx=None):
 
 
 def recover_init(W_init, G_init, tensor_offsets, acc, snap, grad_out, param, exp_avg, exp_avg_sq, param_bf16=0,
-                 flags=0):
+                 flags=0, step_state=0):
     """acc / snap: sequences of W_init device addresses (snap may be None).  Returns (code, ctx)."""
     T = len(tensor_offsets) - 1
     off = (C.c_int64 * (T + 1))(*tensor_offsets)
@@ -121,6 +121,7 @@ def recover_init(W_init, G_init, tensor_offsets, acc, snap, grad_out, param, exp
     cfg.grad_out, cfg.param, cfg.exp_avg, cfg.exp_avg_sq = grad_out or None, param or None, exp_avg or None, exp_avg_sq or None
     cfg.param_bf16 = param_bf16 or None
     cfg.flags = flags
+    cfg.step_state = step_state or None
     ctx = C.c_void_p()
     code = lib().recover_init(C.byref(cfg), C.byref(ctx))
     return code, ctx
@@ -237,7 +238,7 @@ class Shard:
     current stream."""
 
     def __init__(self, W_init, G_init, tensor_offsets, device="cuda:0", snapshots=True, flags=0, param_bf16=False,
-                 host_only=False):
+                 host_only=False, device_step=False):
         import torch
         self.torch = torch
         self.W, self.G = W_init, G_init
@@ -253,11 +254,13 @@ class Shard:
             self.snap = [z() for _ in range(W_init)] if snapshots else None
             self.grad_out, self.param, self.exp_avg, self.exp_avg_sq = z(), z(), z(), z()
             self.param_bf16 = z(torch.bfloat16) if param_bf16 else None
+            self.step_state = torch.zeros(8, dtype=torch.int64, device=device) if device_step else None
             code, self.ctx = recover_init(
                 W_init, G_init, self.off, [t.data_ptr() for t in self.acc],
                 [t.data_ptr() for t in self.snap] if snapshots else None, self.grad_out.data_ptr(),
                 self.param.data_ptr(), self.exp_avg.data_ptr(), self.exp_avg_sq.data_ptr(),
-                self.param_bf16.data_ptr() if param_bf16 else 0, flags)
+                self.param_bf16.data_ptr() if param_bf16 else 0, flags,
+                self.step_state.data_ptr() if device_step else 0)
         if code < 0:
             raise RecoverError(code, recover_last_error(None))
 

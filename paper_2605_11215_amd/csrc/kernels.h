@@ -52,13 +52,53 @@ hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool gra
                              size_t end, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s);
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s);
-hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n,
-                        float decay_mul, float beta1, float one_minus_beta1, float beta2,
-                        float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps, hipStream_t s);
+// Per-step constants of AdamW: decay_mul = 1 - lr wd, step_size = lr / (1 - beta1^t),
+// inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).
+struct AdamArgs {
+  float decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps;
+};
+
+// The constants of the NEXT step from the running products beta1^t, beta2^t (updated in place), in
+// double, with nothing fused, so that the host and the device arrive at the same bits.
+__host__ __device__ inline AdamArgs next_adam_args(double &beta1_pow, double &beta2_pow, float lr, float beta1,
+                                                   float beta2, float eps, float weight_decay) {
+#pragma clang fp contract(off)
+  beta1_pow = beta1_pow * (double)beta1;
+  beta2_pow = beta2_pow * (double)beta2;
+  const double bc1 = 1.0 - beta1_pow, bc2 = 1.0 - beta2_pow;
+  AdamArgs a;
+  const double lw = (double)lr * (double)weight_decay;
+  a.decay_mul = (float)(1.0 - lw);
+  a.beta1 = beta1;
+  a.one_minus_beta1 = (float)(1.0 - (double)beta1);
+  a.beta2 = beta2;
+  a.one_minus_beta2 = (float)(1.0 - (double)beta2);
+  a.step_size = (float)((double)lr / bc1);
+  a.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+  a.eps = eps;
+  return a;
+}
+
+// Optional device-resident step state (64 bytes, caller-owned, zero-filled before the first step): the
+// step count and the running products live on the device, so a captured graph of an iteration advances
+// them on every replay.
+struct StepState {
+  uint64_t step;
+  double beta1_pow, beta2_pow;
+  AdamArgs args;
+  uint64_t reserved;
+};
+static_assert(sizeof(StepState) == 64, "StepState is 64 bytes");
+
+// Advances *st by one step and stores that step's constants in st->args (one thread).
+hipError_t launch_adam_prologue(StepState *st, float lr, float beta1, float beta2, float eps, float weight_decay,
+                                hipStream_t s);
+
+// device_args != nullptr: the kernel reads its constants from device memory instead of `h`.
+hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, const AdamArgs &h,
+                        const AdamArgs *device_args, hipStream_t s);
 
 hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v, uint16_t *p_bf16, bool write_grad,
-                               size_t begin, size_t end, float decay_mul, float beta1, float one_minus_beta1,
-                               float beta2, float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps,
-                               hipStream_t s);
+                               size_t begin, size_t end, const AdamArgs &h, const AdamArgs *device_args, hipStream_t s);
 
 }  // namespace recover

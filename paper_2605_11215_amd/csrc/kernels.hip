@@ -265,9 +265,15 @@ __global__ __launch_bounds__(T) void k_reduce(ReduceArgs a, Span sp, size_t ntil
 // with decay_mul = 1 - lr wd, step_size = lr / (1 - b1^t), inv_sqrt_bc2 = 1 / sqrt(1 - b2^t)
 // prepared in double on the host.
 // ---------------------------------------------------------------------------------------------
-struct AdamArgs {
-  float decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps;
-};
+__global__ void k_adam_prologue(StepState *st, float lr, float beta1, float beta2, float eps, float weight_decay) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    double p1 = st->step ? st->beta1_pow : 1.0, p2 = st->step ? st->beta2_pow : 1.0;
+    st->args = next_adam_args(p1, p2, lr, beta1, beta2, eps, weight_decay);
+    st->beta1_pow = p1;
+    st->beta2_pow = p2;
+    st->step = st->step + 1;
+  }
+}
 
 // The fused multiply-adds are written out so that every kernel that inlines this function rounds
 // in the same places.
@@ -287,7 +293,9 @@ __device__ inline uint32_t f32_to_bf16_rne(float x) {
 template <int T, int U, bool NT, bool BF16OUT>
 __global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__restrict__ m,
                                                     float *__restrict__ v, const float *__restrict__ g,
-                                                    uint16_t *__restrict__ pb, size_t n, AdamArgs h, size_t ntiles) {
+                                                    uint16_t *__restrict__ pb, size_t n, AdamArgs h_arg,
+                                                    const AdamArgs *h_dev, size_t ntiles) {
+  const AdamArgs h = h_dev ? *h_dev : h_arg;
   const size_t nvec = n / 4;
   f32x4 *p4 = reinterpret_cast<f32x4 *>(p), *m4 = reinterpret_cast<f32x4 *>(m), *v4 = reinterpret_cast<f32x4 *>(v);
   const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
@@ -363,7 +371,8 @@ __global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__res
 template <int T, bool NT, bool WRITE_GRAD, bool BF16OUT>
 __global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, float *__restrict__ p, float *__restrict__ m,
                                                     float *__restrict__ v, uint16_t *__restrict__ pb, Span sp,
-                                                    AdamArgs h) {
+                                                    AdamArgs h_arg, const AdamArgs *h_dev) {
+  const AdamArgs h = h_dev ? *h_dev : h_arg;
   const size_t i = size_t(blockIdx.x) * T + threadIdx.x;
   if (i < sp.nvec) {
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
@@ -608,11 +617,15 @@ hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStrea
   return hipGetLastError();
 }
 
-hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, float decay_mul,
-                        float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float step_size,
-                        float inv_sqrt_bc2, float eps, hipStream_t s) {
+hipError_t launch_adam_prologue(StepState *st, float lr, float beta1, float beta2, float eps, float weight_decay,
+                                hipStream_t s) {
+  hipLaunchKernelGGL(k_adam_prologue, dim3(1), dim3(64), 0, s, st, lr, beta1, beta2, eps, weight_decay);
+  return hipGetLastError();
+}
+
+hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, const AdamArgs &h,
+                        const AdamArgs *device_args, hipStream_t s) {
   if (n == 0) return hipSuccess;
-  const AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
   const int Uv = tuning().adamw_vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
@@ -621,26 +634,26 @@ hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *
     constexpr int T = decltype(t)::value, U = decltype(u)::value;
     constexpr bool NT = decltype(nt)::value;
     if (p_bf16)
-      hipLaunchKernelGGL((k_adamw<T, U, NT, true>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+      hipLaunchKernelGGL((k_adamw<T, U, NT, true>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, device_args,
+                         ntiles);
     else
-      hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, ntiles);
+      hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, device_args,
+                         ntiles);
   });
   return hipGetLastError();
 }
 
 hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v, uint16_t *p_bf16, bool write_grad,
-                               size_t begin, size_t end, float decay_mul, float beta1, float one_minus_beta1,
-                               float beta2, float one_minus_beta2, float step_size, float inv_sqrt_bc2, float eps,
+                               size_t begin, size_t end, const AdamArgs &h, const AdamArgs *device_args,
                                hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
-  const AdamArgs h = {decay_mul, beta1, one_minus_beta1, beta2, one_minus_beta2, step_size, inv_sqrt_bc2, eps};
   const size_t tiles = (sp.nvec + 63) / 64;  // one tile per one-wavefront workgroup, no grid cap
   if (tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const unsigned grid = tiles ? (unsigned)tiles : 1u;
   auto go = [&](auto nt, auto wg, auto bf) {
     hipLaunchKernelGGL((k_reduce_adamw<64, decltype(nt)::value, decltype(wg)::value, decltype(bf)::value>), dim3(grid),
-                       dim3(64), 0, s, a, p, m, v, p_bf16, sp, h);
+                       dim3(64), 0, s, a, p, m, v, p_bf16, sp, h, device_args);
   };
   auto with_bf = [&](auto nt, auto wg) {
     if (p_bf16) go(nt, wg, std::true_type{});

@@ -48,6 +48,8 @@ struct recover_ctx {
   uint32_t open_id[kMaxReplicas] = {};
 
   long step = 0;  // optimiser steps taken
+  double beta1_pow = 1.0, beta2_pow = 1.0;      // running products beta^t of the steps taken
+  recover::StepState *step_state = nullptr;     // optional device-resident step state
   std::string err;
 
   // Stream ordering: device calls on one context may come on different streams (the rewind of
@@ -150,14 +152,29 @@ static void fill_decision(const recover_ctx *c, recover_decision *d, bool at_bou
 
 // Orders the work about to be enqueued on `s` after the context's previous device call if that
 // call used another stream: record an event there, make `s` wait for it.  No host wait.
+// While `s` is being captured into a graph, streams outside the capture must not be touched (the
+// runtime would invalidate the capture): the wait is then inserted only if the previous stream
+// belongs to a capture too (a fork inside the same graph); whoever starts a capture has made
+// earlier work finish, as graph capture requires anyway.
 static int order_after_previous(recover_ctx *c, hipStream_t s, const char *who) {
   if (c->host_only) return RECOVER_OK;
+  hipStreamCaptureStatus now = hipStreamCaptureStatusNone;
+  if (s != nullptr && hipStreamIsCapturing(s, &now) != hipSuccess) now = hipStreamCaptureStatusNone;
+  const bool capturing = now == hipStreamCaptureStatusActive;
   if (c->have_last_stream && c->last_stream != s) {
-    hipError_t he = hipSuccess;
-    if (!c->order_event) he = hipEventCreateWithFlags(&c->order_event, hipEventDisableTiming);
-    if (he == hipSuccess) he = hipEventRecord(c->order_event, c->last_stream);
-    if (he == hipSuccess) he = hipStreamWaitEvent(s, c->order_event, 0);
-    if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "%s: stream ordering: %s", who, hipGetErrorString(he));
+    bool insert = true;
+    if (capturing) {
+      hipStreamCaptureStatus prev = hipStreamCaptureStatusNone;
+      insert = c->last_stream != nullptr && hipStreamIsCapturing(c->last_stream, &prev) == hipSuccess &&
+               prev == hipStreamCaptureStatusActive;
+    }
+    if (insert) {
+      hipError_t he = hipSuccess;
+      if (!c->order_event) he = hipEventCreateWithFlags(&c->order_event, hipEventDisableTiming);
+      if (he == hipSuccess) he = hipEventRecord(c->order_event, c->last_stream);
+      if (he == hipSuccess) he = hipStreamWaitEvent(s, c->order_event, 0);
+      if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "%s: stream ordering: %s", who, hipGetErrorString(he));
+    }
   }
   c->last_stream = s;
   c->have_last_stream = true;
@@ -188,7 +205,7 @@ int recover_init(const recover_config *cfg, recover_ctx **out) {
   if (!host_only) {
     if (!cfg->acc || !cfg->grad_out || !cfg->param || !cfg->exp_avg || !cfg->exp_avg_sq)
       return fail(nullptr, RECOVER_ERR_ARG, "recover_init: NULL device buffer");
-    const void *one[] = {cfg->grad_out, cfg->param, cfg->exp_avg, cfg->exp_avg_sq, cfg->param_bf16};
+    const void *one[] = {cfg->grad_out, cfg->param, cfg->exp_avg, cfg->exp_avg_sq, cfg->param_bf16, cfg->step_state};
     for (const void *p : one)
       if (!aligned16(p)) return fail(nullptr, RECOVER_ERR_ALIGN, "recover_init: buffer not 16-byte aligned");
     for (int r = 0; r < cfg->W_init; ++r) {
@@ -222,6 +239,7 @@ int recover_init(const recover_config *cfg, recover_ctx **out) {
     c->exp_avg = cfg->exp_avg;
     c->exp_avg_sq = cfg->exp_avg_sq;
     c->param_bf16 = cfg->param_bf16;
+    c->step_state = reinterpret_cast<recover::StepState *>(cfg->step_state);
   }
   for (int r = 0; r < c->W; ++r) c->role[r] = RECOVER_ROLE_MAJOR;
   c->G_cur = c->G;
@@ -681,25 +699,34 @@ static int check_hyper(recover_ctx *c, float lr, float beta1, float beta2, float
   return RECOVER_OK;
 }
 
-// AdamW constants for step t, prepared in double.
-struct AdamConsts {
-  float decay_mul, one_minus_beta1, one_minus_beta2, step_size, inv_sqrt_bc2;
+// Enqueues what gives this step its AdamW constants.  Host mode: the running products advance in a
+// copy and the constants travel as kernel arguments (*next holds the products to keep if the launch
+// succeeds).  Device mode: a one-thread prologue kernel advances the caller's step state and the
+// update kernel reads the constants from there.
+struct StepConsts {
+  recover::AdamArgs args;
+  const recover::AdamArgs *device_args;
+  double next_beta1_pow, next_beta2_pow;
 };
-static AdamConsts adam_consts(long t, float lr, float beta1, float beta2, float weight_decay) {
-  const double b1 = beta1, b2 = beta2;
-  const double bc1 = 1.0 - pow(b1, (double)t), bc2 = 1.0 - pow(b2, (double)t);
-  AdamConsts k;
-  k.decay_mul = (float)(1.0 - (double)lr * (double)weight_decay);
-  k.one_minus_beta1 = (float)(1.0 - b1);
-  k.one_minus_beta2 = (float)(1.0 - b2);
-  k.step_size = (float)((double)lr / bc1);
-  k.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
-  return k;
+static int prepare_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
+                        hipStream_t stream, StepConsts *k, const char *who) {
+  k->next_beta1_pow = c->beta1_pow;
+  k->next_beta2_pow = c->beta2_pow;
+  k->args = recover::next_adam_args(k->next_beta1_pow, k->next_beta2_pow, lr, beta1, beta2, eps, weight_decay);
+  k->device_args = nullptr;
+  if (c->step_state && !c->host_only) {
+    hipError_t he = recover::launch_adam_prologue(c->step_state, lr, beta1, beta2, eps, weight_decay, stream);
+    if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "%s: %s", who, hipGetErrorString(he));
+    k->device_args = &c->step_state->args;
+  }
+  return RECOVER_OK;
 }
 
 // The optimiser step has been enqueued: the iteration is committed (Alg. 1 line 24).
-static void commit_iteration(recover_ctx *c) {
+static void commit_iteration(recover_ctx *c, const StepConsts &k) {
   c->step += 1;
+  c->beta1_pow = k.next_beta1_pow;
+  c->beta2_pow = k.next_beta2_pow;
   c->pending_advance = c->crossed_boundary;
   open_iteration(c);
 }
@@ -718,14 +745,14 @@ int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float
                   c->red_total[b], want);
   }
   if (int e = order_after_previous(c, (hipStream_t)stream, "adamw_step")) return e;
+  StepConsts k;
+  if (int e = prepare_step(c, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "adamw_step")) return e;
   if (!c->host_only) {
-    const AdamConsts k = adam_consts(c->step + 1, lr, beta1, beta2, weight_decay);
     hipError_t he = recover::launch_adamw(c->param, c->exp_avg, c->exp_avg_sq, c->grad_out, c->param_bf16, (size_t)c->N,
-                                          k.decay_mul, beta1, k.one_minus_beta1, beta2, k.one_minus_beta2, k.step_size,
-                                          k.inv_sqrt_bc2, eps, (hipStream_t)stream);
+                                          k.args, k.device_args, (hipStream_t)stream);
     if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "adamw_step: %s", hipGetErrorString(he));
   }
-  commit_iteration(c);
+  commit_iteration(c, k);
   return RECOVER_OK;
 }
 
@@ -743,19 +770,18 @@ int recover_reduce_adamw_step(recover_ctx *c, float lr, float beta1, float beta2
       return fail(c, RECOVER_ERR_STATE, "reduce_adamw_step: tensor %d holds %d microbatches, Eq. 1 needs %d", b,
                   microbatches_in(c, b), want);
   if (int e = order_after_previous(c, (hipStream_t)stream, "reduce_adamw_step")) return e;
-  const AdamConsts k = adam_consts(c->step + 1, lr, beta1, beta2, weight_decay);
+  StepConsts k;
+  if (int e = prepare_step(c, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "reduce_adamw_step")) return e;
   for (const ReduceGroup &g : groups) {
     if (!c->host_only) {
       hipError_t he = recover::launch_reduce_adamw(g.a, c->param, c->exp_avg, c->exp_avg_sq, c->param_bf16,
                                                    flags & RECOVER_FUSED_WRITE_GRAD, (size_t)c->off[g.b],
-                                                   (size_t)c->off[g.e], k.decay_mul, beta1, k.one_minus_beta1, beta2,
-                                                   k.one_minus_beta2, k.step_size, k.inv_sqrt_bc2, eps,
-                                                   (hipStream_t)stream);
+                                                   (size_t)c->off[g.e], k.args, k.device_args, (hipStream_t)stream);
       if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "reduce_adamw_step: %s", hipGetErrorString(he));
     }
     note_reduced(c, g, false);
   }
-  commit_iteration(c);
+  commit_iteration(c, k);
   return RECOVER_OK;
 }
 

@@ -483,3 +483,74 @@ def test_device_compare_matches_numpy():
         ok = ~(np.isnan(x) | np.isnan(y))
         assert got["max_abs_diff"] == (np.max(np.abs(x[ok] - y[ok])) if ok.any() else 0.0)
         assert got["max_abs_ref"] == (np.max(np.abs(y[ok])) if ok.any() else 0.0)
+
+
+def test_device_step_state_gives_the_same_bits_as_host_constants():
+    torch = torch_()
+    N = OFF[-1]
+    g = grads_np(43, N, 1e-3, False)
+    res = []
+    for dev in (False, True):
+        p0 = S.fill(N, 43, S.TAG_PARAM, 0, 0, 0.02)
+        s = B.Shard(4, 2, OFF, device_step=dev)
+        s.param[:N].copy_(torch.from_numpy(p0))
+        eng = HipEngine(s)
+        for t in range(4):
+            run_iteration(eng, view_hip, t, g, 4, hp=hp32(), fuse=bool(t % 2))
+        res.append([x.clone() for x in (s.param, s.exp_avg, s.exp_avg_sq)])
+        if dev:
+            st = s.step_state.cpu().numpy()
+            assert st[0] == 4                                            # four steps counted on the device
+            assert abs(st[1:3].view(np.float64)[0] - 0.9 ** 4) < 1e-7    # running product of beta1 (as fp32 0.9)
+    for x, y in zip(*res):
+        assert torch.equal(x, y)
+
+
+def test_hip_graph_replay_of_a_whole_iteration():
+    """A launch-bound shard: one iteration (accumulate_many per microbatch slot, snapshot, one-pass
+    reduce+AdamW) captured into a HIP graph and replayed with new gradient contents, with eager work of
+    a twin context and synchronisation between the replays; every replay equals the eager twin."""
+    torch = torch_()
+    off = [0, 1000, 4099, 4100]
+    N, W, G = off[-1], 4, 2
+    p0 = S.fill(N, 47, S.TAG_PARAM, 0, 0, 0.02)
+    twins = []
+    for dev in (True, False):
+        s = B.Shard(W, G, off, device_step=dev)
+        s.param[:N].copy_(torch.from_numpy(p0))
+        twins.append(s)
+    s_graph, s_eager = twins
+    bufs = [[torch.zeros(N + 4, device="cuda") for _ in range(W)] for _ in range(G)]
+
+    def iteration(s):
+        for k in range(G):
+            s.accumulate_many(list(range(W)), [r + W * k for r in range(W)], bufs[k])
+        s.snapshot()
+        s.reduce_adamw_step(write_grad=True, **hp32())
+        s.advance()
+
+    def load(t):
+        for k in range(G):
+            for r in range(W):
+                bufs[k][r][:N].copy_(torch.from_numpy(S.fill(N, 47, S.TAG_GRAD, r + W * k, t, 1e-3)))
+
+    load(0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration(s_graph)
+    for t in range(5):
+        load(t)
+        graph.replay()
+        iteration(s_eager)
+        torch.cuda.synchronize()
+        for x, y in ((s_graph.grad_out, s_eager.grad_out), (s_graph.param, s_eager.param),
+                     (s_graph.exp_avg, s_eager.exp_avg), (s_graph.exp_avg_sq, s_eager.exp_avg_sq)):
+            assert torch.equal(x, y), t
+    assert int(s_graph.step_state.cpu()[0]) == 5
+    # the context is still usable eagerly after the capture (its books are at an iteration start)
+    load(5)
+    iteration(s_graph)
+    iteration(s_eager)
+    torch.cuda.synchronize()
+    assert torch.equal(s_graph.param, s_eager.param)
