@@ -209,7 +209,7 @@ def main():
     k_gbs = dict(accumulate_first=W * (s_g + 4) * N / phase[0] / 1e6, accumulate_rmw=(s_g + 8) * N / rmw_ms / 1e6,
                  reduce=bpe["reduce"] * N / phase[2] / 1e6, adamw=28 * N / phase[3] / 1e6)
 
-    # the same iteration with a snapshot of every replica before the reduction (Alg. 1 lines 9-10)
+    # the same iteration with a snapshot of every replica before the reduction (Alg. 1, snapshot step)
     for _ in range(2):
         iteration(snapshot=True)
     torch.cuda.synchronize()

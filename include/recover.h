@@ -7,12 +7,12 @@
  * The calls below are the numeric statements of one iteration of the paper's protocol
  * (Alg. 1) with the forward/backward pass replaced by a gradient handed in by the caller:
  *
- *   recover_accumulate     Alg. 1 lines 3-5   local accumulation, dropped once the quota is met
- *   recover_snapshot       Alg. 1 lines 9-10  S(b) <- b, tag eps(b) <- eps_cur            (Sec. 4.2)
- *   recover_reduce         Alg. 2 "Reduce"    sum over non-spare survivors, then / B     (Alg. 1 line 24)
+ *   recover_accumulate     Alg. 1, local accumulation   local accumulation, dropped once the quota is met
+ *   recover_snapshot       Alg. 1, snapshot step  S(b) <- b, tag eps(b) <- eps_cur            (Sec. 4.2)
+ *   recover_reduce         Alg. 2 "Reduce"    sum over non-spare survivors, then / B     (Alg. 1, commit step)
  *   recover_policy_adjust  Alg. 2 "Record", Alg. 4, Alg. 6 (failure set given) or Alg. 7 (empty set)
  *   recover_restore        Alg. 5             stale = {b : eps(b) < eps_cur}; copy S(b) -> b
- *   recover_adamw_step     Alg. 1 line 24     optimiser step; ends the iteration
+ *   recover_adamw_step     Alg. 1, commit step     optimiser step; ends the iteration
  *
  * Notation is the paper's (Sec. 4.3): W_init replicas, G_init microbatches per replica,
  * B = W_init * G_init microbatches per iteration (constant for the life of a context, Eq. 1),
@@ -53,7 +53,7 @@ typedef struct recover_ctx recover_ctx; /* opaque, library-owned, freed by recov
 
 enum {
   RECOVER_OK = 0,
-  RECOVER_SKIPPED = 1,          /* quota already met (Alg. 1 line 5) or group quiesced (Alg. 2 line 1) */
+  RECOVER_SKIPPED = 1,          /* quota already met (Alg. 1, quota test) or group quiesced (Alg. 2, quiesce test) */
   RECOVER_ERR_ARG = -1,         /* bad pointer, range, replica index, dtype or flag */
   RECOVER_ERR_STATE = -2,       /* call not allowed in the current protocol state */
   RECOVER_ERR_NO_SURVIVOR = -3, /* the failure set would leave no replica (Sec. 4, Claim) */
@@ -134,9 +134,9 @@ typedef struct {
 int recover_init(const recover_config *cfg, recover_ctx **out);
 int recover_destroy(recover_ctx *ctx);
 
-/* Alg. 1 lines 3-5.  acc[replica][i] += widen(grad[i]) for i in tensors [tensor_begin, tensor_end);
+/* Alg. 1, local accumulation.  acc[replica][i] += widen(grad[i]) for i in tensors [tensor_begin, tensor_end);
  * the first microbatch of a replica in an iteration stores (+0) + widen(grad[i]) instead, which
- * replaces "zero gradients" of Alg. 1 line 1.  `grad` is a device pointer to the FLAT gradient
+ * replaces "zero gradients" of Alg. 1, start of the iteration.  `grad` is a device pointer to the FLAT gradient
  * of the whole shard (n_elems elements of `dtype`), indexed like acc.  A microbatch may arrive
  * in several calls over disjoint tensor ranges, all with the same id; it counts as contributed
  * once every tensor has taken it.  Returns SKIPPED when contributed >= target.  ERR_STATE: dead
@@ -156,13 +156,13 @@ int recover_accumulate_many(recover_ctx *ctx, int n, const int32_t *replicas, co
                             const void *const *grads, int dtype, int32_t *status_out, void *hip_stream);
 
 /* recover_accumulate followed by recover_snapshot of the same replica and tensor range in ONE pass: the
- * new accumulator value is stored to acc and to snap (Alg. 1 lines 3-5 and 9-10 fused; 4 bytes per element
+ * new accumulator value is stored to acc and to snap (Alg. 1: local accumulation and snapshot in one pass; 4 bytes per element
  * less than the two calls).  Same results, bookkeeping and errors as the two calls; ERR_NO_SNAPSHOT
  * without snapshot buffers.  For callers that snapshot at every microbatch boundary. */
 int recover_accumulate_snapshot(recover_ctx *ctx, int replica, uint32_t global_mb_id, const void *grad, int dtype,
                                 int tensor_begin, int tensor_end, void *hip_stream);
 
-/* Alg. 1 lines 9-10, Sec. 4.2.  snap[r][range] <- acc[r][range]; records (eps_cur, microbatch
+/* Alg. 1, snapshot step, Sec. 4.2.  snap[r][range] <- acc[r][range]; records (eps_cur, microbatch
  * count) per (replica, tensor).  replica = -1: every survivor. */
 int recover_snapshot(recover_ctx *ctx, int replica, int tensor_begin, int tensor_end, void *hip_stream);
 
@@ -182,14 +182,14 @@ int recover_restore(recover_ctx *ctx, int replica, int stale_only, void *hip_str
  * recover_adamw_step of such an iteration before the next accumulate.  Host only. */
 int recover_policy_adjust(recover_ctx *ctx, const int32_t *failed, int n_failed, recover_decision *out);
 
-/* Alg. 2 "Reduce" and the division of Alg. 1 line 24.  For tensors [tensor_begin, tensor_end):
+/* Alg. 2 "Reduce" and the division of Alg. 1, commit step.  For tensors [tensor_begin, tensor_end):
  * grad_out[i] = (sum over contributing survivors r, ascending, of acc[r][i]) / B, contributors =
  * majors and minors that hold at least one microbatch in that tensor.  RECOVER_REDUCE_INPLACE also
  * leaves the undivided sum in every survivor's acc (what an all-reduce does; needed to model a
  * failure during synchronisation).  SKIPPED while quiesced. */
 int recover_reduce(recover_ctx *ctx, int tensor_begin, int tensor_end, uint32_t flags, void *hip_stream);
 
-/* Alg. 1 line 24.  Decoupled-weight-decay Adam on (param, exp_avg, exp_avg_sq) with grad_out, step
+/* Alg. 1, commit step.  Decoupled-weight-decay Adam on (param, exp_avg, exp_avg_sq) with grad_out, step
  * count kept by the context (from 1).  ERR_STATE unless every tensor was reduced under the current
  * epoch, is unchanged since, and holds exactly B microbatches (Eq. 1).  Ends the iteration:
  * counters, quotas, snapshot records and boundary-minor marks are reset. */

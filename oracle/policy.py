@@ -28,7 +28,7 @@ class NoSurvivor(Exception):
 
 
 def smallest_G_cur(W_cur, B):
-    """Alg. 7 step 1: count G up until W_cur * G >= B."""
+    """Alg. 7, choice of G_cur: count G up until W_cur * G >= B."""
     G = 1
     while W_cur * G < B:
         G += 1
@@ -105,7 +105,7 @@ class World:
 
     # ---- iteration lifecycle -----------------------------------------------------
     def begin_iteration(self):
-        """Alg. 1 line 1: counters to zero, quotas from the roles (Sec. 4.3)."""
+        """Alg. 1, start of the iteration: counters to zero, quotas from the roles (Sec. 4.3)."""
         W = self.W_init
         self.contributed = [0] * W
         self.target = [self.quota_of_role(self.role[r]) for r in range(W)]
@@ -115,7 +115,7 @@ class World:
         self.restore_mode = RESTORE_SKIP
 
     def should_contribute(self, r):
-        """Alg. 1 lines 4-5: accumulate while the quota is not met."""
+        """Alg. 1, quota test: accumulate while the quota is not met."""
         return self.role[r] != DEAD and self.contributed[r] < self.target[r]
 
     def C_cur(self):
@@ -193,12 +193,12 @@ class World:
 
     # ---- commit ------------------------------------------------------------------
     def commit(self):
-        """Alg. 1 line 24 has run; start the next iteration's counters."""
+        """Alg. 1's commit step has run; start the next iteration's counters."""
         self.pending_advance = self.crossed_boundary
         self.begin_iteration()
 
     def advance(self):
-        """Alg. 1 lines 25-27 / Alg. 7: only after an iteration that crossed a boundary."""
+        """Alg. 1 after the commit / Alg. 7: only after an iteration that crossed a boundary."""
         if self.pending_advance:
             lay = policy_advancement(len(self.alive()), self.B)
             self.G_cur, self.R_cur = lay["G_cur"], lay["R_cur"]

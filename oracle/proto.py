@@ -5,13 +5,13 @@ a gradient accumulator per replica, a snapshot per replica, and the bookkeeping 
 Sec. 4.2 (snapshot + world-epoch tag per bucket; here a bucket is one tensor of the
 shard).  The steps are those of Alg. 1 in the paper's order:
 
-  accumulate   Alg. 1 lines 3-5   local accumulation, skipped once the quota is met
-  snapshot     Alg. 1 lines 9-10  S(b) <- b, tag eps(b) <- eps_cur
+  accumulate   Alg. 1, local accumulation   local accumulation, skipped once the quota is met
+  snapshot     Alg. 1, snapshot step  S(b) <- b, tag eps(b) <- eps_cur
   reduce       Alg. 2 Reduce      sum over non-spare survivors; `inplace` leaves the sum
                                   in every survivor's bucket as an all-reduce does
   on_failure   Alg. 2 Record, Alg. 4, Alg. 6
   restore      Alg. 5             stale = {b : eps(b) < eps_cur}; copy S(b) -> b
-  commit       Alg. 1 line 24     divide by the constant B, optimiser step
+  commit       Alg. 1, commit step     divide by the constant B, optimiser step
   advance      Alg. 7
 
 `dtype` is the arithmetic type of accumulate and reduce: float64 is the reference value,
@@ -78,7 +78,7 @@ class Proto:
         self.m = np.zeros(self.N, self.state_dtype) if m is None else np.array(m, self.state_dtype)
         self.v = np.zeros(self.N, self.state_dtype) if v is None else np.array(v, self.state_dtype)
 
-    # ------------------------------------------------------------------ Alg. 1 lines 3-5
+    # ------------------------------------------------------------------ Alg. 1, local accumulation
     def accumulate(self, r, mb_id, g, tb=0, te=None):
         """Add microbatch `mb_id`'s gradient `g` (flat, length N, any float type) into
         replica r's accumulator over tensors [tb, te).  Returns False when the replica
@@ -116,7 +116,7 @@ class Proto:
             w.contributed[r] = k + 1
         return True
 
-    # ------------------------------------------------------------------ Alg. 1 lines 9-10
+    # ------------------------------------------------------------------ Alg. 1, snapshot step
     def snapshot(self, r=None, tb=0, te=None):
         w = self.world
         tb, te = self._rng(tb, te)
@@ -137,7 +137,7 @@ class Proto:
     # ------------------------------------------------------------------ Alg. 2, Reduce
     def reduce(self, tb=0, te=None, inplace=False):
         """Sum the contributors' buckets in ascending replica order and divide by B.
-        Returns False (no-op) while the group is quiesced (Alg. 2 line 1)."""
+        Returns False (no-op) while the group is quiesced (Alg. 2, quiesce test)."""
         w = self.world
         tb, te = self._rng(tb, te)
         if self.quiesced:
@@ -215,7 +215,7 @@ class Proto:
             w.restore_mode = RESTORE_SKIP
         return n
 
-    # ------------------------------------------------------------------ Alg. 1 line 24
+    # ------------------------------------------------------------------ Alg. 1, commit step
     def ready_to_commit(self):
         """Every bucket reduced once under the current membership, unchanged since, and
         holding exactly B microbatches (Eq. 1; Sec. 4.2 restoration invariant)."""

@@ -95,7 +95,7 @@ static int finished_by_contributors(const recover_ctx *c) {
   return n;
 }
 
-// Alg. 1 line 1: a new iteration.  Counters to zero, quotas from the roles, bookkeeping cleared.
+// Alg. 1, start of the iteration: a new iteration.  Counters to zero, quotas from the roles, bookkeeping cleared.
 static void open_iteration(recover_ctx *c) {
   for (int r = 0; r < c->W; ++r) {
     c->contributed[r] = 0;
@@ -722,7 +722,7 @@ static int prepare_step(recover_ctx *c, float lr, float beta1, float beta2, floa
   return RECOVER_OK;
 }
 
-// The optimiser step has been enqueued: the iteration is committed (Alg. 1 line 24).
+// The optimiser step has been enqueued: the iteration is committed (Alg. 1, commit step).
 static void commit_iteration(recover_ctx *c, const StepConsts &k) {
   c->step += 1;
   c->beta1_pow = k.next_beta1_pow;

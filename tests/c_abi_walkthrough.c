@@ -8,7 +8,7 @@
 
 static uint32_t next_id = 0; /* ids only have to ascend within a replica */
 
-/* Every live replica accumulates until its quota is met (Alg. 1 lines 3-5). */
+/* Every live replica accumulates until its quota is met (Alg. 1, local accumulation). */
 static int fill_quota(recover_ctx *ctx, int W, const int32_t *role) {
   int r, k;
   for (r = 0; r < W; ++r) {
