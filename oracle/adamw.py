@@ -1,6 +1,6 @@
 """Oracle: one decoupled-weight-decay Adam (AdamW) step in fp64 (test infrastructure only).
 
-Alg. 1's commit step says only "optimizer step"; the benchmark configuration names AdamW, so the
+Alg. 1's commit step names no optimiser; the benchmark configuration names AdamW, so the
 oracle is the textbook definition (Loshchilov & Hutter, "Decoupled Weight Decay
 Regularization", Alg. 2 with the schedule multiplier folded into lr), step count t from 1:
 
