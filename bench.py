@@ -329,6 +329,9 @@ def main():
                    "replicas": W, "microbatches": M, "n_elems": N, "n_tensors": T,
                    "bytes_per_elem": bpe["total"], "grad_pool_buffers": POOL},
         "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "paper_context": "context only, other hardware: the paper reports 2.23x effective throughput over "
+                         "checkpoint-restart after successive failures (128 x A100-40GB, 7B LLaMA-style model) and "
+                         "evaluates up to 512 GPUs; it gives no bandwidth or per-kernel figure for this path",
         "settle": {"seconds": settle_s, "windows": settle_windows, "untimed": True},
         "microbatches_per_s": M / (dt / a.steps),
         "kernel_GBps": k_gbs,
