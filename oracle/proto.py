@@ -74,6 +74,7 @@ class Proto:
         return tb, te
 
     def set_state(self, param, m=None, v=None):
+        """Optimiser state (parameters and the two moments), kept in `state_dtype` between steps."""
         self.param = np.array(param, self.state_dtype)
         self.m = np.zeros(self.N, self.state_dtype) if m is None else np.array(m, self.state_dtype)
         self.v = np.zeros(self.N, self.state_dtype) if v is None else np.array(v, self.state_dtype)
@@ -227,13 +228,14 @@ class Proto:
         return not self.quiesced
 
     def committed_ids(self):
-        """The multiset A(t) of the proof sketch: ids inside the contributors' buffers."""
+        """The multiset A(t) of the proof-sketch appendix: ids inside the contributors' buffers."""
         out = []
         for r in self.world.contributors():
             out.extend(self.ids[r])
         return out
 
     def committed_ids_by_replica(self):
+        """phi_t of the proof-sketch appendix: replica -> the microbatches it contributes."""
         return {r: list(self.ids[r]) for r in self.world.contributors()}
 
     def adamw_step(self, lr, beta1, beta2, eps, weight_decay):
@@ -249,4 +251,5 @@ class Proto:
         self._begin_iteration_buffers()
 
     def advance(self):
+        """Alg. 7, after an iteration that crossed a policy boundary."""
         return self.world.advance()

@@ -15,7 +15,6 @@ namespace recover {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-
 Tuning &tuning() {
   static Tuning t;
   return t;
@@ -86,7 +85,7 @@ template <typename G, int T, int U, bool NT, bool FIRST, bool SNAP>
 __global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, float *__restrict__ snap,
                                                   const G *__restrict__ g, Span sp, size_t ntiles, int xcd_chunked) {
   f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
-  f32x4 *s4 = reinterpret_cast<f32x4 *>(snap + sp.vbegin);
+  f32x4 *s4 = SNAP ? reinterpret_cast<f32x4 *>(snap + sp.vbegin) : nullptr;
   const G *gv = g + sp.vbegin;
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
   size_t first = blockIdx.x, stride = gridDim.x;

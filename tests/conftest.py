@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The libraries are built in-tree beforehand; only if nothing is built at all (a fresh checkout)
+    # are they compiled here, once.
+    from paper_2605_11215_amd import build
+    if not (os.path.exists(build.LIB) and os.path.exists(build.SYNTH_LIB)):
+        build.build_all()
 
 
 def pytest_collection_modifyitems(config, items):
