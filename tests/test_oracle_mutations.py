@@ -147,6 +147,7 @@ CASES = [
 ]
 
 
+@pytest.mark.filterwarnings("ignore::RuntimeWarning")          # a planted mistake may take sqrt of a negative
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_planted_mistake_is_caught(case):
     module, old, new, pins = CASES[case]
