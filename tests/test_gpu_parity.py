@@ -554,3 +554,25 @@ def test_hip_graph_replay_of_a_whole_iteration():
     iteration(s_eager)
     torch.cuda.synchronize()
     assert torch.equal(s_graph.param, s_eager.param)
+
+
+def test_failure_reported_between_iterations_case_b():
+    """Failure after a complete synchronisation (Sec. 4.2 case (b)): the step commits with the lost
+    replica's gradients, the failure is declared before the next iteration's first microbatch."""
+    N = OFF[-1]
+    o, s, eng = make_pair(4, 2, OFF, False, seed=53)
+    g = grads_np(53, N, 1e-3, False)
+    for t in range(2):
+        before = state_of(s, N)
+        a = run_iteration(o, view_oracle, t, g, 4, hp=hp32())
+        b = run_iteration(eng, view_hip, t, g, 4, hp=hp32())
+        assert a["ids"] == b["ids"]
+        compare_iteration(o, s, N, before)
+        if t == 0:
+            assert sorted(sum(b["ids"].values(), [])) == list(range(8))
+            da, db = o.on_failure([2]), eng.on_failure([2])
+            for k in da:
+                assert da[k] == db[k], k
+            o.restore(None)
+            eng.restore(None)
+    assert b["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}

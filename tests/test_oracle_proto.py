@@ -316,3 +316,20 @@ def test_reduction_under_an_older_epoch_cannot_be_committed():
     p.reduce()
     assert terms_of((p.grad_out * 12)[0]) == [0, 2, 3, 4, 6, 8, 9, 10, 12, 14, 15, 16]
     p.adamw_step(**HP)
+
+
+def test_failure_after_synchronisation_is_handled_in_the_next_iteration():
+    """Sec. 4.2 case (b): every bucket was reduced in the original world, so the iteration commits
+    with the lost replica's microbatches inside; the failure is declared at the start of the next
+    iteration, which then runs an extended loop from its first slot."""
+    off = [0, 3, 5]
+    p = new_proto(4, 2, off=off)
+    out = run_iteration(p, view_oracle, 0, coded(5), 4)
+    assert terms_of((p.grad_out * 8)[0]) == list(range(8))          # replica 2's ids 2 and 6 included
+    d = p.on_failure([2])                                           # learnt after the step
+    assert d["at_boundary"] and d["C_cur"] == 0 and d["G_ext"] == 1 and d["n_bdry"] == 1
+    p.restore(None)
+    out = run_iteration(p, view_oracle, 1, coded(5), 4)
+    assert out["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
+    assert terms_of((p.grad_out * 8)[0]) == [0, 1, 3, 4, 5, 7, 8, 9]
+    assert p.world.G_cur == 3 and p.world.role == [0, 0, 4, 1]
