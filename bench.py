@@ -10,8 +10,9 @@ buffers before the timed region: generating them stands in for the backward pass
 Prints ONE JSON line: effective HBM GB/s = algorithmic bytes per iteration / time, with a
 `roofline` object for the dominant kernel (the read-modify-write accumulate, timed with
 events on the launch stream inside the timed region) and a `cpu_baseline` object (the CPU
-oracle, as it stands, on a bounded slice of the same workload).  Extra keys report each
-kernel's rate and the same iteration with a snapshot of every replica, timed separately.
+oracle, as it stands, on a bounded slice of the same workload).  Extra keys, each timed
+separately after the headline region: every kernel's rate, the iteration with a snapshot of every
+replica, the one-pass variants, the non-blocking rewind, and one whole failure iteration.
 """
 import argparse
 import json
@@ -321,6 +322,24 @@ def main():
                            what="restore of %d replicas + generation of one gradient + reduce" % W)
     assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], stream) == 0
 
+    # One failure iteration of this workload's schedule, timed as a whole (Alg. 1 with Alg. 4-6): two
+    # replicas crash after two microbatches, half of the tensors are snapshotted and all-reduced in
+    # place before the failure shows, then rewind, extended pass, snapshot, reduce, AdamW, advancement.
+    failure_iteration = None
+    if W >= 4 and G >= 2:
+        from paper_2605_11215_amd.loop import run_iteration, view_shard
+        lost = {W // 2 - 1: min(2, G), W - 2: min(2, G)}
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        res = run_iteration(sh, view_shard, 0, lambda t, mb: pool[mb % POOL], W, dying=lost, fidelity_k=T // 2 or 1,
+                            hp=HP)
+        torch.cuda.synchronize()
+        dtf2 = time.perf_counter() - t4
+        n_acc = sum(len(v) for v in res["ids"].values()) + sum(lost.values())
+        failure_iteration = dict(ms=dtf2 * 1e3, lost_replicas=sorted(lost), accumulates=n_acc,
+                                 committed_microbatches=sum(len(v) for v in res["ids"].values()),
+                                 extra_slots=res["decisions"][0]["G_ext"], vs_failure_free=dtf2 / (dt / a.steps))
+
     out = {
         "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
@@ -341,6 +360,7 @@ def main():
         "fused_snapshot_every_microbatch": every,
         "batched_launches": batched,
         "nonblocking_restore": restore_overlap,
+        "failure_iteration": failure_iteration,
         "roofline": {"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % ("bf16" if c["bf16"] else "float"), "achieved": k_gbs["accumulate_rmw"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
                      "traffic": read_traffic() if a.workload == 2 else None, "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,
