@@ -7,12 +7,19 @@
  * The calls below are the numeric statements of one iteration of the paper's protocol
  * (Alg. 1) with the forward/backward pass replaced by a gradient handed in by the caller:
  *
- *   recover_accumulate     Alg. 1, local accumulation   local accumulation, dropped once the quota is met
- *   recover_snapshot       Alg. 1, snapshot step  S(b) <- b, tag eps(b) <- eps_cur            (Sec. 4.2)
- *   recover_reduce         Alg. 2 "Reduce"    sum over non-spare survivors, then / B     (Alg. 1, commit step)
+ *   recover_accumulate     Alg. 1, local accumulation: acc += gradient, dropped once the quota is met
+ *   recover_snapshot       Alg. 1, snapshot step (Sec. 4.2): S(b) <- b, tag eps(b) <- eps_cur
+ *   recover_reduce         Alg. 2 "Reduce" and the division of Alg. 1's commit step: sum over non-spare
+ *                          survivors, then / B
  *   recover_policy_adjust  Alg. 2 "Record", Alg. 4, Alg. 6 (failure set given) or Alg. 7 (empty set)
- *   recover_restore        Alg. 5             stale = {b : eps(b) < eps_cur}; copy S(b) -> b
- *   recover_adamw_step     Alg. 1, commit step     optimiser step; ends the iteration
+ *   recover_restore        Alg. 5: stale = {b : eps(b) < eps_cur}; copy S(b) -> b
+ *   recover_adamw_step     Alg. 1, commit step: optimiser step; ends the iteration
+ *
+ * plus one-pass variants that give the same bits as the calls they replace
+ * (recover_accumulate_snapshot, recover_accumulate_many, recover_reduce_adamw_step), queries, and a
+ * device-side buffer comparison for verification.  Every device call only launches kernels (no
+ * allocation, no memset, no host wait), so a sequence of calls can be captured into a HIP graph;
+ * see recover_config.step_state for what the optimiser step needs then.
  *
  * Notation is the paper's (Sec. 4.3): W_init replicas, G_init microbatches per replica,
  * B = W_init * G_init microbatches per iteration (constant for the life of a context, Eq. 1),
