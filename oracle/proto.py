@@ -5,13 +5,13 @@ a gradient accumulator per replica, a snapshot per replica, and the bookkeeping 
 Sec. 4.2 (snapshot + world-epoch tag per bucket; here a bucket is one tensor of the
 shard).  The steps are those of Alg. 1 in the paper's order:
 
-  accumulate   Alg. 1, local accumulation   local accumulation, skipped once the quota is met
-  snapshot     Alg. 1, snapshot step  S(b) <- b, tag eps(b) <- eps_cur
-  reduce       Alg. 2 Reduce      sum over non-spare survivors; `inplace` leaves the sum
-                                  in every survivor's bucket as an all-reduce does
+  accumulate   Alg. 1, local accumulation: skipped once the quota is met
+  snapshot     Alg. 1, snapshot step: S(b) <- b, tag eps(b) <- eps_cur
+  reduce       Alg. 2, Reduce: sum over non-spare survivors; `inplace` leaves the sum in every
+               survivor's bucket as an all-reduce does
   on_failure   Alg. 2 Record, Alg. 4, Alg. 6
-  restore      Alg. 5             stale = {b : eps(b) < eps_cur}; copy S(b) -> b
-  commit       Alg. 1, commit step     divide by the constant B, optimiser step
+  restore      Alg. 5: stale = {b : eps(b) < eps_cur}; copy S(b) -> b
+  commit       Alg. 1, commit step: divide by the constant B, optimiser step
   advance      Alg. 7
 
 `dtype` is the arithmetic type of accumulate and reduce: float64 is the reference value,

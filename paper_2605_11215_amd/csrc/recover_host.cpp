@@ -95,7 +95,7 @@ static int finished_by_contributors(const recover_ctx *c) {
   return n;
 }
 
-// Alg. 1, start of the iteration: a new iteration.  Counters to zero, quotas from the roles, bookkeeping cleared.
+// Alg. 1, start of the iteration: counters to zero, quotas from the roles, bookkeeping cleared.
 static void open_iteration(recover_ctx *c) {
   for (int r = 0; r < c->W; ++r) {
     c->contributed[r] = 0;

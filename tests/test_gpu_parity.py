@@ -421,7 +421,7 @@ def test_random_call_sequences_agree_with_the_oracle_on_the_gpu():
 
 
 def test_bucketed_arrival_in_reverse_order_with_failure_during_the_bucket_loop():
-    """The paper's bucket loop (Alg. 1, bucket loop, walk-through appendix): gradients arrive bucket by
+    """The paper's bucket loop (Alg. 1; walk-through appendix): gradients arrive bucket by
     bucket in reverse order, each bucket is snapshotted and all-reduced in place as soon as the last
     microbatch has produced it; a replica fails after some buckets were reduced.  300 tensors of
     0..40 elements in 13 buckets: every bucket boundary is ragged."""
