@@ -13,7 +13,7 @@ def pytest_configure(config):
     # The libraries are built in-tree beforehand; only if nothing is built at all (a fresh checkout)
     # are they compiled here, once.
     from paper_2605_11215_amd import build
-    if not (os.path.exists(build.LIB) and os.path.exists(build.SYNTH_LIB)):
+    if not (os.path.exists(build.LIB) and os.path.exists(build.SYNTH_LIB) and os.path.exists(build.EXAMPLE)):
         build.build_all()
 
 

@@ -576,3 +576,14 @@ def test_failure_reported_between_iterations_case_b():
             o.restore(None)
             eng.restore(None)
     assert b["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
+
+
+def test_cpp_program_on_the_c_abi_without_python():
+    """The prebuilt C++ example (hipMalloc'd buffers, no PyTorch): two iterations with a failure,
+    checked inside the program against the constant-gradient closed form."""
+    import os
+    import subprocess
+    from paper_2605_11215_amd import build
+    assert os.path.exists(build.EXAMPLE), "run python -m paper_2605_11215_amd.build first"
+    r = subprocess.run([build.EXAMPLE], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.returncode, r.stdout, r.stderr)
