@@ -95,19 +95,26 @@ static int finished_by_contributors(const recover_ctx *c) {
   return n;
 }
 
-// Alg. 1, start of the iteration: counters to zero, quotas from the roles, bookkeeping cleared.
-static void open_iteration(recover_ctx *c) {
+// Quotas and counters of a new iteration from the role layout in force (Sec. 4.3).
+static void prime_quotas(recover_ctx *c) {
   for (int r = 0; r < c->W; ++r) {
     c->contributed[r] = 0;
     c->target[r] = quota_of(c, c->role[r]);
     c->bdry_minor[r] = false;
-    c->ids[r].clear();
-    c->open_mb[r] = false;
   }
   c->loop_bound = c->G_cur;
   c->crossed_boundary = false;
-  c->quiesced = false;
   c->restore_mode = RECOVER_RESTORE_SKIP;
+}
+
+// Alg. 1, start of the iteration: counters to zero, quotas from the roles, bookkeeping cleared.
+static void open_iteration(recover_ctx *c) {
+  prime_quotas(c);
+  for (int r = 0; r < c->W; ++r) {
+    c->ids[r].clear();
+    c->open_mb[r] = false;
+  }
+  c->quiesced = false;
   std::fill(c->cnt.begin(), c->cnt.end(), 0);
   std::fill(c->snap_valid.begin(), c->snap_valid.end(), 0);
   std::fill(c->holds_sum.begin(), c->holds_sum.end(), 0);
@@ -520,10 +527,10 @@ int recover_policy_adjust(recover_ctx *c, const int32_t *failed, int n_failed, r
   if (!c) return RECOVER_ERR_ARG;
   if (n_failed < 0 || (n_failed > 0 && !failed)) return fail(c, RECOVER_ERR_ARG, "policy_adjust: bad failure set");
   if (n_failed == 0) {  // commit-time advancement
-    if (c->pending_advance) {
+    if (c->pending_advance) {  // the iteration is already open (the commit opened it): only the layout changes
       advancement(c);
       c->pending_advance = false;
-      open_iteration(c);
+      prime_quotas(c);
     }
     fill_decision(c, out, false, 0, 0);
     return RECOVER_OK;

@@ -244,15 +244,15 @@ def test_random_call_sequences_agree_with_the_oracle_host_only():
             return self.s.accumulate(r, mb, None, tb, te, snapshot=snapshot)
 
     total = {"ok": 0, "err": 0, "steps": 0, "failures": 0}
-    for seed in range(40):
-        W, G = [(4, 2), (8, 1), (3, 3), (6, 2), (2, 4)][seed % 5]
-        off = [0, 3, 8, 8, 20]
+    for seed in range(60):
+        W, G = [(4, 2), (8, 1), (3, 3), (6, 2), (2, 4), (16, 1), (5, 2)][seed % 7]
+        off = [0, 3, 8, 8, 20, 21, 40]
         s = B.Shard(W, G, off, host_only=True, flags=B.FLAG_ADAPTIVE if seed % 8 == 7 else 0)
         st = differential.run(seed, 400, W, G, off, HostOnly(s), adaptive=(seed % 8 == 7))
         for k in total:
             total[k] += st[k]
         s.close()
-    assert total["ok"] > 8000 and total["err"] > 500 and total["steps"] > 200 and total["failures"] > 40, total
+    assert total["ok"] > 12000 and total["err"] > 500 and total["steps"] > 300 and total["failures"] > 60, total
 
 
 def test_stale_reduction_and_rewound_audit_in_the_library():
@@ -291,3 +291,44 @@ def test_stale_reduction_and_rewound_audit_in_the_library():
     s2.restore(0, stale_only=False)
     assert B.recover_committed_ids(s2.ctx, 0)[1] == [0] and s2.query()["contributed"][0] == 1
     assert s2.accumulate(0, 2, None)
+
+
+def test_snapshot_taken_between_commit_and_advancement_survives_the_advancement():
+    """Advancement installs the next role layout; it does not reopen the iteration the commit opened
+    (found by the random-call test: the oracle kept such a snapshot record, the library dropped it)."""
+    off = [0, 4, 8]
+    g = np.zeros(8, np.float32)
+    o = Proto(3, 2, off, dtype=np.float32)
+    o.set_state(g)
+    s = B.Shard(3, 2, off, host_only=True)
+
+    class E:
+        def __getattr__(self, k):
+            return getattr(s, k)
+
+        def accumulate(self, r, mb, grad, tb=0, te=None, snapshot=False):
+            return s.accumulate(r, mb, None, tb, te)
+
+    e = E()
+    # an iteration that crosses a boundary, stopped before the advancement
+    for eng in (o, e):
+        for k in range(2):
+            for r in range(3):
+                if not (r == 2 and k == 1):
+                    eng.accumulate(r, r + 3 * k, g)
+        eng.on_failure([2])
+        eng.restore(None)
+        for r in (0, 1):
+            v = view_oracle(o) if eng is o else view_hip(s)
+            while v["contributed"][r] < v["target"][r]:
+                eng.accumulate(r, 100 + r + 3 * v["contributed"][r], g)
+                v = view_oracle(o) if eng is o else view_hip(s)
+        eng.reduce()
+        eng.adamw_step(**HP)
+        eng.snapshot(None, 0, 1)              # between the commit and the advancement
+        eng.advance()
+        eng.accumulate(0, 0, g)
+    # a rewind of replica 0 now goes back to the empty bucket 0 but bucket 1 holds a microbatch: refused by both
+    with pytest.raises(ProtocolError):
+        o.restore(0, stale_only=False)
+    assert B.recover_restore(s.ctx, 0, 0) == B.ERR_STATE
