@@ -51,6 +51,7 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
     stats = {"ok": 0, "err": 0, "steps": 0, "failures": 0}
     n_acc = 0
     kinds = ["acc", "snap", "restore", "reduce", "fail", "step", "advance", "bad"]
+    one_pass = hasattr(lib_engine, "reduce_adamw_step")      # also exercise the one-pass forms of the library
     for i in range(n_ops):
         w = o.world
         alive = w.alive()
@@ -63,7 +64,27 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
         te = int(rng.integers(tb, T + 1))
         if rng.random() < 0.6:
             tb, te = 0, T
-        if kind == "acc":
+        if kind == "acc" and one_pass and not w.pending_advance and rng.random() < 0.12:
+            # one accumulate_many call against separate accumulates (only pairs the oracle will accept)
+            free = [q for q in alive if o.cur_id[q] is None and not any(o.inplace_sum[q])]
+            if len(free) >= 2:
+                pick = [int(x) for x in rng.choice(free, size=int(rng.integers(2, len(free) + 1)), replace=False)]
+                ids = [(o.ids[q][-1] + W) if o.ids[q] else q for q in pick]
+                gs = [grads(n_acc + j) if grads else None for j in range(len(pick))]
+                n_acc += len(pick)
+                ra = [o.accumulate(q, mb, zero if g is None else g) for q, mb, g in zip(pick, ids, gs)]
+                rb = lib_engine.accumulate_many(pick, ids, gs if grads else None) if any(ra) else None
+                if rb is None:                               # every pair skipped: the library says SKIPPED
+                    code, _ = B.recover_accumulate_many(lib_engine.ctx, pick, ids, [0] * len(pick), B.F32) \
+                        if not grads else (B.SKIPPED, None)
+                    assert code == B.SKIPPED
+                    rb = [False] * len(pick)
+                assert [bool(x) for x in ra] == [bool(x) for x in rb], (seed, i, "many", ra, rb)
+                a = b = ("ok", None)
+                kind = "many"
+        if kind == "many":
+            pass
+        elif kind == "acc":
             todo = [q for q in alive if w.contributed[q] < w.target[q]]
             if todo and rng.random() < 0.9:
                 r = int(rng.choice(todo))
@@ -79,7 +100,12 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
             g = grads(n_acc) if grads else None
             n_acc += 1
             a = call(o.accumulate, r, mb, zero if g is None else g, tb, te)
-            b = call(lib_engine.accumulate, r, mb, g, tb, te)
+            if one_pass and rng.random() < 0.15:             # accumulate+snapshot in one pass
+                b = call(lib_engine.accumulate, r, mb, g, tb, te, snapshot=True)
+                if a[0] == "ok" and a[1]:
+                    o.snapshot(r, tb, te)
+            else:
+                b = call(lib_engine.accumulate, r, mb, g, tb, te)
         elif kind == "snap":
             rr = None if rng.random() < 0.5 else r
             a, b = call(o.snapshot, rr, tb, te), call(lib_engine.snapshot, rr, tb, te)
@@ -104,6 +130,15 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
                 for key in a[1]:
                     assert a[1][key] == b[1][key], (seed, i, key)
                 a = b = ("ok", None)
+        elif kind == "step" and one_pass and rng.random() < 0.4 and not o.quiesced and not w.pending_advance \
+                and all(w.contributed[q] == w.target[q] for q in w.contributors()) \
+                and not any(o.inplace_sum[q][b_] for q in alive for b_ in range(T)) \
+                and all(o.cur_id[q] is None for q in w.contributors()):
+            # reduce + AdamW in one pass against the two calls (a state in which both succeed)
+            o.reduce()
+            a, b = call(o.adamw_step, **HP32), call(lib_engine.reduce_adamw_step, write_grad=True, **HP32)
+            if a[0] == "ok":
+                stats["steps"] += 1
         elif kind == "step":
             a, b = call(o.adamw_step, **HP32), call(lib_engine.adamw_step, **HP32)
             if a[0] == "ok":

@@ -243,6 +243,9 @@ def test_random_call_sequences_agree_with_the_oracle_host_only():
         def accumulate(self, r, mb, g, tb=0, te=None, snapshot=False):
             return self.s.accumulate(r, mb, None, tb, te, snapshot=snapshot)
 
+        def accumulate_many(self, replicas, ids, grads):
+            return self.s.accumulate_many(replicas, ids, None)
+
     total = {"ok": 0, "err": 0, "steps": 0, "failures": 0}
     for seed in range(60):
         W, G = [(4, 2), (8, 1), (3, 3), (6, 2), (2, 4), (16, 1), (5, 2)][seed % 7]
