@@ -40,12 +40,15 @@ def sensible_next(o, rng):
     return "step"
 
 
-def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, adaptive=False):
+def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, adaptive=False,
+        grad_of_id=None, oracle_dtype=np.float32, before_commit=None):
     """lib_engine: object with Shard's methods (accumulate takes the NumPy gradient or None).
-    grads(i) -> float32 array for the i-th accumulate, or None on host-only contexts."""
+    grads(i) -> float32 array for the i-th accumulate, or None on host-only contexts;
+    grad_of_id(mb) -> the gradient of microbatch mb (then used instead of grads);
+    before_commit(o) is called when a step is about to succeed (the reduction is complete)."""
     rng = np.random.default_rng(seed)
     T = len(off) - 1
-    o = Proto(W, G, off, dtype=np.float32, static=not adaptive)
+    o = Proto(W, G, off, dtype=oracle_dtype, static=not adaptive)
     o.set_state(np.zeros(off[-1], np.float32))
     zero = np.zeros(off[-1], np.float32)
     stats = {"ok": 0, "err": 0, "steps": 0, "failures": 0}
@@ -70,7 +73,8 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
             if len(free) >= 2:
                 pick = [int(x) for x in rng.choice(free, size=int(rng.integers(2, len(free) + 1)), replace=False)]
                 ids = [(o.ids[q][-1] + W) if o.ids[q] else q for q in pick]
-                gs = [grads(n_acc + j) if grads else None for j in range(len(pick))]
+                gs = [grad_of_id(mb) if grad_of_id else (grads(n_acc + j) if grads else None)
+                      for j, mb in enumerate(ids)]
                 n_acc += len(pick)
                 ra = [o.accumulate(q, mb, zero if g is None else g) for q, mb, g in zip(pick, ids, gs)]
                 rb = lib_engine.accumulate_many(pick, ids, gs if grads else None) if any(ra) else None
@@ -97,7 +101,7 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
                 mb = (o.ids[r][-1] + W) if o.ids[r] else r
                 if rng.random() < 0.04:
                     mb = max(0, mb - W)
-            g = grads(n_acc) if grads else None
+            g = grad_of_id(mb) if grad_of_id else (grads(n_acc) if grads else None)
             n_acc += 1
             a = call(o.accumulate, r, mb, zero if g is None else g, tb, te)
             if one_pass and rng.random() < 0.15:             # accumulate+snapshot in one pass
@@ -136,10 +140,14 @@ def run(seed, n_ops, W, G, off, lib_engine, grads=None, compare_buffers=None, ad
                 and all(o.cur_id[q] is None for q in w.contributors()):
             # reduce + AdamW in one pass against the two calls (a state in which both succeed)
             o.reduce()
+            if before_commit and o.ready_to_commit():
+                before_commit(o)
             a, b = call(o.adamw_step, **HP32), call(lib_engine.reduce_adamw_step, write_grad=True, **HP32)
             if a[0] == "ok":
                 stats["steps"] += 1
         elif kind == "step":
+            if before_commit and o.ready_to_commit():
+                before_commit(o)
             a, b = call(o.adamw_step, **HP32), call(lib_engine.adamw_step, **HP32)
             if a[0] == "ok":
                 stats["steps"] += 1

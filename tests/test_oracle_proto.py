@@ -333,3 +333,60 @@ def test_failure_after_synchronisation_is_handled_in_the_next_iteration():
     assert out["ids"] == {0: [0, 4, 8], 1: [1, 5, 9], 3: [3, 7]}
     assert terms_of((p.grad_out * 8)[0]) == [0, 1, 3, 4, 5, 7, 8, 9]
     assert p.world.G_cur == 3 and p.world.role == [0, 0, 4, 1]
+
+
+def test_random_call_sequences_commit_each_audited_microbatch_exactly_once():
+    """The restoration invariant under random (not scripted) call sequences: partial ranges, partial
+    microbatches, snapshots, in-place reductions, failures, rewinds.  Microbatch j carries 2**(j mod 52)
+    scaled per round of 52, so at every commit the reduced gradient, read as an integer, must be
+    exactly the sum over the audited ids: each once, nothing of a dead replica, nothing rewound."""
+    from tests import differential
+
+    class Mirror:
+        """A second oracle behind the library-side interface (the harness needs two engines)."""
+
+        def __init__(self, W, G, off):
+            self.p = Proto(W, G, off, dtype=np.float64)
+            self.p.set_state(np.zeros(off[-1], np.float32))
+            self.W = W
+
+        def query(self):
+            w = self.p.world
+            return dict(role=list(w.role), target=list(w.target), contributed=list(w.contributed),
+                        loop_bound=w.loop_bound, epoch=w.eps)
+
+        def _replica(self, r):
+            if r is not None and not 0 <= r < self.W:
+                raise ProtocolError("replica index")
+            return r
+
+        def accumulate(self, r, mb, g, tb=0, te=None, snapshot=False):
+            return self.p.accumulate(self._replica(r), mb, g, tb, te)
+
+        def snapshot(self, r=None, tb=0, te=None):
+            return self.p.snapshot(self._replica(r), tb, te)
+
+        def restore(self, r=None, stale_only=True):
+            return self.p.restore(self._replica(r), stale_only)
+
+        def __getattr__(self, k):
+            return getattr(self.p, k)
+
+    off = [0, 2, 3, 3, 7]
+    checked = 0
+    for seed in range(30):
+        W, G = [(4, 2), (2, 4), (8, 1), (4, 4)][seed % 4]        # B a power of two: the division is exact
+
+        def code(mb):
+            return np.full(off[-1], float(2 ** (mb % 52)) * (1 + (mb // 52)), np.float64)
+
+        def check(o):
+            nonlocal checked
+            want = sum(float(2 ** (j % 52)) * (1 + j // 52) for j in o.committed_ids())
+            assert len(o.committed_ids()) == o.world.B
+            assert np.all(o.grad_out * o.world.B == want), (seed, o.committed_ids())
+            checked += 1
+
+        differential.run(700 + seed, 300, W, G, off, Mirror(W, G, off), grad_of_id=code, oracle_dtype=np.float64,
+                         before_commit=check)
+    assert checked > 100
