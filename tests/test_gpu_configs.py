@@ -76,10 +76,12 @@ def test_config_matches_oracle_on_sampled_elements(cid):
     s.close()
 
 
-def test_largest_shard_every_element_constant_gradient():
+@pytest.mark.parametrize("one_pass", [False, True])
+def test_largest_shard_every_element_constant_gradient(one_pass):
     """Config 5's shape (1,978,662,912 elements, 259 tensors, byte offsets past 2^32): constant
     bf16 gradients and constant parameters make every output element one known value, so the
-    whole buffers are checked, with a failure and an extended pass in between."""
+    whole buffers are checked, with a failure and an extended pass in between.  one_pass: through
+    the accumulate+snapshot and reduce+AdamW kernels instead of the separate ones."""
     import torch
     c = CONFIGS[5]
     W, G, off = c["W"], c["G"], c["off"]
@@ -89,7 +91,8 @@ def test_largest_shard_every_element_constant_gradient():
     cval = 0.375
     g = torch.full((N,), cval, dtype=torch.bfloat16, device="cuda")
     eng = HipEngine(s, True)
-    run_iteration(eng, view_hip, 0, lambda t, mb: g, W, hp=hp32(), dying={1: 2}, fidelity_k=100)
+    run_iteration(eng, view_hip, 0, lambda t, mb: g, W, hp=hp32(), dying={1: 2}, fidelity_k=100,
+                  snapshot_every=one_pass, fuse=one_pass)
     go = s.grad_out[:N]
     assert float(go.min()) == cval and float(go.max()) == cval
     p, m, v = oracle_adamw.adamw_step(np.float32(0.5), 0.0, 0.0, np.float32(cval), 1, **hp32())
@@ -99,6 +102,8 @@ def test_largest_shard_every_element_constant_gradient():
     for r in (0, 2, 3):
         a = s.acc[r][:N]
         assert float(a.min()) == float(a.max())
+        if one_pass:
+            assert B.compare_tensors(s.snap[r], s.acc[r], N)["n_mismatch"] == 0
     s.close()
 
 
