@@ -66,7 +66,7 @@ enum {
   RECOVER_ERR_NO_SURVIVOR = -3, /* the failure set would leave no replica (Sec. 4, Claim) */
   RECOVER_ERR_HIP = -4,         /* a HIP runtime call failed */
   RECOVER_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
-  RECOVER_ERR_NO_SNAPSHOT = -6  /* the context was created without snapshot buffers */
+  RECOVER_ERR_NO_SNAPSHOT = -6  /* the call needs snapshot buffers and the context was created without */
 };
 
 enum { RECOVER_F32 = 0, RECOVER_BF16 = 1 }; /* element type of a microbatch gradient */
@@ -99,7 +99,8 @@ typedef struct {
   int32_t n_tensors;             /* >= 1 */
   const int64_t *tensor_offsets; /* host, n_tensors + 1 non-decreasing element offsets from 0; copied */
   float *const *acc;             /* host array of W_init device pointers, n_elems floats each */
-  float *const *snap;            /* host array of W_init device pointers, or NULL (no snapshots) */
+  float *const *snap;            /* host array of W_init device pointers, or NULL (no snapshots); with
+                                    RECOVER_FLAG_HOST_ONLY only the presence of the array counts */
   float *grad_out;               /* device, n_elems floats: the iteration gradient */
   float *param;                  /* device, n_elems floats: fp32 master parameters */
   float *exp_avg;                /* device, n_elems floats: AdamW first moment */
@@ -178,7 +179,9 @@ int recover_snapshot(recover_ctx *ctx, int replica, int tensor_begin, int tensor
  * <- the snapshot's, so work accumulated after the snapshot is as if never accumulated.  Lifts
  * the quiesce; in NON-BLOCKING mode the replica's snapshot records are then cleared (the extended
  * pass takes fresh ones).  ERR_STATE if the rewind would leave a replica's tensors at different
- * microbatch counts (nothing is copied then). */
+ * microbatch counts (nothing is copied then).  On a context without snapshot buffers nothing was
+ * ever snapshotted, so the stale set is empty (Alg. 5, SKIP): the call only lifts the quiesce, and
+ * returns ERR_NO_SNAPSHOT if a bucket holds an in-place sum that it cannot take back. */
 int recover_restore(recover_ctx *ctx, int replica, int stale_only, void *hip_stream);
 
 /* n_failed > 0: Alg. 2 "Record" + Alg. 4 + Alg. 6 for the failure set failed[0..n_failed)
@@ -235,12 +238,30 @@ int recover_compare(const float *x, const float *ref, int64_t n, recover_compare
 /* Message of the last negative return on this context (or of recover_init if ctx == NULL). */
 const char *recover_last_error(const recover_ctx *ctx);
 
-/* Launch-shape knobs for measurement sweeps (process-wide; values outside the documented sets are
- * rejected with ERR_ARG).  key 0: accumulate vectors per lane {1,2,4}; key 1: nontemporal loads/stores
- * {0,1}; key 2: grid cap in workgroups, 0 = one tile per workgroup; keys 3, 4, 5: vectors per lane of the
- * reduce, AdamW and copy kernels {1,2,4}; key 6: XCD-chunked tile order of accumulate {0,1}; key 7: lanes
- * per workgroup {64,256}.  The results do not depend on any of them. */
+/* Launch-shape knobs, for measurement sweeps only.  They are PROCESS-GLOBAL (shared by every context) and not
+ * thread-safe: set them while no other thread is inside the library.  The results never depend on them.  Values
+ * outside the documented sets are rejected with ERR_ARG and change nothing. */
+enum { /* kernel classes that have a launch shape of their own */
+  RECOVER_KERNEL_ACCUMULATE_FIRST_F32 = 0, /* first microbatch of a replica: no read of acc */
+  RECOVER_KERNEL_ACCUMULATE_RMW_F32 = 1,
+  RECOVER_KERNEL_ACCUMULATE_FIRST_BF16 = 2,
+  RECOVER_KERNEL_ACCUMULATE_RMW_BF16 = 3,
+  RECOVER_KERNEL_COPY = 4, /* snapshot and restore */
+  RECOVER_KERNEL_REDUCE = 5,
+  RECOVER_KERNEL_ADAMW = 6,
+  RECOVER_KERNEL_REDUCE_ADAMW = 7,
+  RECOVER_KERNEL_CLASSES = 8
+};
+enum { /* keys of recover_set_tuning / recover_get_tuning */
+  RECOVER_TUNE_NONTEMPORAL = 1, /* {0, 1}: streaming cache hints on loads and stores */
+  RECOVER_TUNE_GRID_CAP = 2,    /* 0 = one tile per workgroup, else grid-stride over at most this many workgroups */
+  RECOVER_TUNE_XCD_CHUNKED = 6, /* {0, 1}: accumulate gives each XCD one contiguous eighth of the range */
+  RECOVER_TUNE_THREADS = 7,     /* {64, 256}: lanes per workgroup */
+  RECOVER_TUNE_VECS = 16,       /* + kernel class: 128-bit vectors per lane per stream {1, 2, 4} */
+  RECOVER_TUNE_WAVES = 32       /* + kernel class: wavefronts resident per CU, 0 = hardware limit, else 2..32 */
+};
 int recover_set_tuning(int key, int value);
+int recover_get_tuning(int key, int *value);
 
 #ifdef __cplusplus
 }

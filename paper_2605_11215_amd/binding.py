@@ -22,12 +22,16 @@ REDUCE_INPLACE = 1
 MAX_REPLICAS = 64
 
 FUSED_WRITE_GRAD = 1
+(KERNEL_ACCUMULATE_FIRST_F32, KERNEL_ACCUMULATE_RMW_F32, KERNEL_ACCUMULATE_FIRST_BF16, KERNEL_ACCUMULATE_RMW_BF16,
+ KERNEL_COPY, KERNEL_REDUCE, KERNEL_ADAMW, KERNEL_REDUCE_ADAMW, KERNEL_CLASSES) = range(9)
+TUNE_NONTEMPORAL, TUNE_GRID_CAP, TUNE_XCD_CHUNKED, TUNE_THREADS, TUNE_VECS, TUNE_WAVES = 1, 2, 6, 7, 16, 32
 
 EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_accumulate_many",
            "recover_accumulate_snapshot",
            "recover_reduce_adamw_step", "recover_snapshot", "recover_restore",
            "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
-           "recover_committed_ids", "recover_compare", "recover_last_error", "recover_set_tuning"]
+           "recover_committed_ids", "recover_compare", "recover_last_error", "recover_set_tuning",
+           "recover_get_tuning"]
 
 
 class RecoverError(RuntimeError):
@@ -84,6 +88,7 @@ def lib():
         L.recover_last_error.argtypes = [P]
         L.recover_last_error.restype = C.c_char_p
         L.recover_set_tuning.argtypes = [I, I]
+        L.recover_get_tuning.argtypes = [I, C.POINTER(C.c_int)]
         for name in EXPORTS:
             if name != "recover_last_error":
                 getattr(L, name).restype = I
@@ -200,10 +205,14 @@ def recover_query(ctx, W_init):
     return code, _decision_dict(d, arrs)
 
 
-def recover_committed_ids(ctx, replica, cap=4096):
-    buf = (C.c_uint32 * cap)()
-    n = lib().recover_committed_ids(ctx, replica, buf, cap)
-    return n, list(buf[:max(0, min(n, cap))])
+def recover_committed_ids(ctx, replica, cap=64):
+    """Returns (count or negative code, all ids): asks again with a larger array when the count exceeds it."""
+    while True:
+        buf = (C.c_uint32 * max(1, cap))()
+        n = lib().recover_committed_ids(ctx, replica, buf, cap)
+        if n <= cap:
+            return n, list(buf[:max(0, n)])
+        cap = n
 
 
 class CompareResult(C.Structure):
@@ -230,6 +239,13 @@ def recover_set_tuning(key, value):
     return lib().recover_set_tuning(key, value)
 
 
+def recover_get_tuning(key):
+    """Returns (code, value)."""
+    v = C.c_int(0)
+    code = lib().recover_get_tuning(key, C.byref(v))
+    return code, v.value
+
+
 class Shard:
     """Buffers of one context allocated with PyTorch on `device`, plus the calls on it.
 
@@ -247,7 +263,9 @@ class Shard:
         self.host_only = host_only
         if host_only:
             flags |= FLAG_HOST_ONLY
-            code, self.ctx = recover_init(W_init, G_init, self.off, None, None, 0, 0, 0, 0, 0, flags)
+            # no device memory at all; the presence of the snap array alone says "with snapshots"
+            code, self.ctx = recover_init(W_init, G_init, self.off, None, [0] * W_init if snapshots else None,
+                                          0, 0, 0, 0, 0, flags)
         else:
             z = lambda dt=torch.float32: torch.zeros(max(self.N, 4), dtype=dt, device=device)
             self.acc = [z() for _ in range(W_init)]

@@ -42,7 +42,8 @@ def build_synth():
 def build_example():
     """A plain C++ program on the C ABI (no Python, no PyTorch), linked against librecover.so."""
     src = os.path.join(HERE, "csrc", "example_iteration.cpp")
-    _run([HIPCC, "-O2", "-std=c++17", "--offload-arch=gfx950", "-x", "hip", src, "-o", EXAMPLE, "-L", HERE, "-lrecover",
+    _run([HIPCC, "-O2", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-x", "hip", src, "-o", EXAMPLE, "-L", HERE, "-lrecover",
           "-Wl,-rpath,$ORIGIN"])
     return EXAMPLE
 

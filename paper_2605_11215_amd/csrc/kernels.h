@@ -9,16 +9,35 @@ namespace recover {
 
 constexpr int kMaxReplicas = 64;
 
+// Kernel classes with a launch shape of their own (index of Tuning::shape).
+enum KernelClass {
+  kAccFirstF32 = 0,  // accumulate, first microbatch (no read of acc), fp32 gradient
+  kAccRmwF32,        // accumulate, read-modify-write, fp32 gradient
+  kAccFirstBf16,
+  kAccRmwBf16,
+  kCopy,             // snapshot / restore
+  kReduce,
+  kAdamw,
+  kReduceAdamw,
+  kNumClasses
+};
+
+// vecs: 128-bit vectors each lane keeps in flight per stream {1, 2, 4}.
+// waves: wavefronts resident per CU, 0 = as many as the hardware takes (32).  HBM efficiency falls once
+// much more than ~48 KiB of loads per CU are in flight (the open DRAM pages thrash), so the kernels
+// with several streams per wavefront run faster with fewer resident wavefronts.  The limit is imposed by
+// giving every workgroup a share of the CU's 160 KiB of LDS that it never touches.
+struct Shape {
+  int vecs, waves;
+};
+
 struct Tuning {
-  int threads = 64;         // lanes per workgroup: 64 (one wavefront) or 256
-  int vecs_per_thread = 1;  // accumulate: 128-bit vectors each lane keeps in flight per stream
-  int nontemporal = 1;      // streaming cache hints on loads and stores
-  int grid_cap = 0;         // 0: one tile per workgroup; else grid-stride over at most this many
-  int reduce_vecs = 1;      // reduce: vectors per lane (each with up to 8 contributor loads in flight)
-  int adamw_vecs = 1;       // AdamW: vectors per lane (four loads each)
-  int copy_vecs = 1;        // snapshot / restore copy: vectors per lane
-  int xcd_chunked = 0;      // accumulate: 1 = workgroup b works in the b%8-th eighth of the range (one
-                            // contiguous region per XCD) instead of tile b
+  int threads = 64;     // lanes per workgroup: 64 (one wavefront) or 256
+  int nontemporal = 1;  // streaming cache hints on loads and stores
+  int grid_cap = 0;     // 0: one tile per workgroup; else grid-stride over at most this many
+  int xcd_chunked = 0;  // accumulate: 1 = workgroup b works in the b%8-th eighth of the range (one
+                        // contiguous region per XCD) instead of tile b
+  Shape shape[kNumClasses] = {{1, 0}, {1, 24}, {1, 0}, {1, 0}, {1, 0}, {1, 0}, {1, 10}, {1, 8}};
 };
 Tuning &tuning();
 
@@ -51,6 +70,13 @@ hipError_t launch_accumulate_many(const AccumulateManyArgs &a, int n_pairs, bool
 hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool grad_is_bf16, bool first, size_t begin,
                              size_t end, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s);
+
+// dst[i][begin, end) = src[i][begin, end) for n_pairs buffer pairs in one launch.
+struct CopyManyArgs {
+  float *dst[kMaxReplicas];
+  const float *src[kMaxReplicas];
+};
+hipError_t launch_copy_many(const CopyManyArgs &a, int n_pairs, size_t begin, size_t end, hipStream_t s);
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s);
 // Per-step constants of AdamW: decay_mul = 1 - lr wd, step_size = lr / (1 - beta1^t),
 // inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).

@@ -6,6 +6,12 @@
 // use, 64-bit element indices (a shard can exceed 2^32 bytes), no LDS (no element is used twice) and
 // no atomics (the sums have a fixed order).  Ranges that do not start or end on a 16-byte boundary
 // get their ragged ends from a few lanes of workgroup 0.
+//
+// Every kernel body exists twice, selected by a wavefront-uniform test: FULL tiles (all but at most
+// the last one) run without any per-lane bounds test, so all their loads are issued back to back
+// before the first wait; the last, partial tile masks each access.  Raw bf16 words are widened only
+// after every load of the tile has been issued (widening right after the load would put a wait
+// between the gradient load and the accumulator load).
 #include "kernels.h"
 
 #include <type_traits>
@@ -58,23 +64,41 @@ __device__ inline void st(T *p, T v) {
     *p = v;
 }
 
+using True = std::true_type;
+using False = std::false_type;
+
+// Runs body(True) on a full tile and body(False) on the partial one; `full` is wavefront-uniform.
+template <typename F>
+__device__ inline void on_tile(bool full, F &&body) {
+  if (full)
+    body(True{});
+  else
+    body(False{});
+}
+
 __device__ inline float bf16_to_f32(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
 
-// Four gradient elements of vector i, widened to fp32.
-template <bool NT>
-__device__ inline f32x4 load_grad(const float *g, size_t i) {
-  return ld<NT>(reinterpret_cast<const f32x4 *>(g) + i);
-}
-template <bool NT>
-__device__ inline f32x4 load_grad(const uint16_t *g, size_t i) {
-  u32x2 w = ld<NT>(reinterpret_cast<const u32x2 *>(g) + i);
-  f32x4 r;
-  r.x = __builtin_bit_cast(float, w.x << 16);
-  r.y = __builtin_bit_cast(float, w.x & 0xFFFF0000u);
-  r.z = __builtin_bit_cast(float, w.y << 16);
-  r.w = __builtin_bit_cast(float, w.y & 0xFFFF0000u);
-  return r;
-}
+// Four gradient elements as they lie in memory (fp32: one 128-bit vector; bf16: one 64-bit vector),
+// and their fp32 values.
+template <typename G>
+struct Grad4;
+template <>
+struct Grad4<float> {
+  typedef f32x4 raw;
+  __device__ static inline f32x4 widen(raw w) { return w; }
+};
+template <>
+struct Grad4<uint16_t> {
+  typedef u32x2 raw;
+  __device__ static inline f32x4 widen(raw w) {
+    f32x4 r;
+    r.x = __builtin_bit_cast(float, w.x << 16);
+    r.y = __builtin_bit_cast(float, w.x & 0xFFFF0000u);
+    r.z = __builtin_bit_cast(float, w.y << 16);
+    r.w = __builtin_bit_cast(float, w.y & 0xFFFF0000u);
+    return r;
+  }
+};
 __device__ inline float load_grad1(const float *g, size_t i) { return g[i]; }
 __device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to_f32(g[i]); }
 
@@ -82,38 +106,49 @@ __device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to
 // accumulate: acc[i] = acc[i] + widen(g[i]);  FIRST: acc[i] = (+0) + widen(g[i])
 // ---------------------------------------------------------------------------------------------
 template <typename G, int T, int U, bool NT, bool FIRST, bool SNAP>
-__global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, float *__restrict__ snap,
-                                                  const G *__restrict__ g, Span sp, size_t ntiles, int xcd_chunked) {
+__device__ inline void accumulate_tiles(float *__restrict__ acc, float *__restrict__ snap, const G *__restrict__ g,
+                                        const Span &sp, size_t first, size_t stride, size_t ntiles) {
+  typedef typename Grad4<G>::raw Raw;
   f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
   f32x4 *s4 = SNAP ? reinterpret_cast<f32x4 *>(snap + sp.vbegin) : nullptr;
-  const G *gv = g + sp.vbegin;
+  const Raw *g4 = reinterpret_cast<const Raw *>(g + sp.vbegin);
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+  for (size_t tile = first; tile < ntiles; tile += stride) {
+    const size_t base = tile * size_t(T * U) + threadIdx.x;
+    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
+      constexpr bool FULL = decltype(full)::value;
+      Raw x[U];
+      f32x4 a[U];
+      bool ok[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) x[u] = ld<NT>(g4 + base + size_t(T) * u);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) a[u] = FIRST ? zero : ld<NT>(a4 + base + size_t(T) * u);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (ok[u]) {
+          const f32x4 r = a[u] + Grad4<G>::widen(x[u]);
+          st<NT>(a4 + base + size_t(T) * u, r);
+          if (SNAP) st<NT>(s4 + base + size_t(T) * u, r);
+        }
+      }
+    });
+  }
+}
+
+template <typename G, int T, int U, bool NT, bool FIRST, bool SNAP>
+__global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, float *__restrict__ snap,
+                                                  const G *__restrict__ g, Span sp, size_t ntiles, int xcd_chunked) {
   size_t first = blockIdx.x, stride = gridDim.x;
   if (xcd_chunked) {  // grid = 8 * ceil(ntiles / 8): one tile per workgroup, XCD x owns the x-th eighth
     first = size_t(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
     stride = ntiles;
   }
-  for (size_t tile = first; tile < ntiles; tile += stride) {
-    const size_t base = tile * size_t(T * U) + threadIdx.x;
-    f32x4 x[U], a[U];
-    bool ok[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = base + size_t(T) * u < sp.nvec;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) x[u] = load_grad<NT>(gv, base + size_t(T) * u);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) a[u] = FIRST ? zero : ld<NT>(a4 + base + size_t(T) * u);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (ok[u]) {
-        const f32x4 r = a[u] + x[u];
-        st<NT>(a4 + base + size_t(T) * u, r);
-        if (SNAP) st<NT>(s4 + base + size_t(T) * u, r);
-      }
-    }
-  }
+  accumulate_tiles<G, T, U, NT, FIRST, SNAP>(acc, snap, g, sp, first, stride, ntiles);
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t i = ragged_index(sp, threadIdx.x);
     if (i < sp.end) {
@@ -133,18 +168,14 @@ __global__ __launch_bounds__(T) void k_accumulate_many(AccumulateManyArgs a, Spa
   const int pair = blockIdx.y;
   float *acc = a.acc[pair];
   const G *g = static_cast<const G *>(a.grad[pair]);
-  const bool first = a.first[pair] != 0;
-  const size_t i = size_t(blockIdx.x) * T + threadIdx.x;
-  if (i < sp.nvec) {
-    f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin) + i;
-    const f32x4 x = load_grad<NT>(g + sp.vbegin, i);
-    f32x4 av = {0.f, 0.f, 0.f, 0.f};
-    if (!first) av = ld<NT>(a4);
-    st<NT>(a4, av + x);
-  }
+  const size_t ntiles = (sp.nvec + T - 1) / T;
+  if (a.first[pair])
+    accumulate_tiles<G, T, 1, NT, true, false>(acc, nullptr, g, sp, blockIdx.x, gridDim.x, ntiles);
+  else
+    accumulate_tiles<G, T, 1, NT, false, false>(acc, nullptr, g, sp, blockIdx.x, gridDim.x, ntiles);
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t e = ragged_index(sp, threadIdx.x);
-    if (e < sp.end) acc[e] = (first ? 0.f : acc[e]) + load_grad1(g, e);
+    if (e < sp.end) acc[e] = (a.first[pair] ? 0.f : acc[e]) + load_grad1(g, e);
   }
 }
 
@@ -152,25 +183,24 @@ __global__ __launch_bounds__(T) void k_accumulate_many(AccumulateManyArgs a, Spa
 // copy (snapshot and restore): dst[i] = src[i]
 // ---------------------------------------------------------------------------------------------
 template <int T, int U, bool NT>
-__global__ __launch_bounds__(T) void k_copy(float *__restrict__ dst, const float *__restrict__ src, Span sp,
-                                                   size_t ntiles) {
+__device__ inline void copy_tiles(float *__restrict__ dst, const float *__restrict__ src, const Span &sp, size_t ntiles) {
   f32x4 *d4 = reinterpret_cast<f32x4 *>(dst + sp.vbegin);
   const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + sp.vbegin);
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const size_t base = tile * size_t(T * U) + threadIdx.x;
-    f32x4 x[U];
-    if (base + size_t(T) * (U - 1) < sp.nvec) {
+    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
+      constexpr bool FULL = decltype(full)::value;
+      f32x4 x[U];
+      bool ok[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) x[u] = ld<NT>(s4 + base + size_t(T) * u);
+      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
 #pragma unroll
-      for (int u = 0; u < U; ++u) st<NT>(d4 + base + size_t(T) * u, x[u]);
-    } else {
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) x[u] = ld<NT>(s4 + base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const size_t i = base + size_t(T) * u;
-        if (i < sp.nvec) st<NT>(d4 + i, ld<NT>(s4 + i));
-      }
-    }
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) st<NT>(d4 + base + size_t(T) * u, x[u]);
+    });
   }
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t i = ragged_index(sp, threadIdx.x);
@@ -178,72 +208,95 @@ __global__ __launch_bounds__(T) void k_copy(float *__restrict__ dst, const float
   }
 }
 
+template <int T, int U, bool NT>
+__global__ __launch_bounds__(T) void k_copy(float *__restrict__ dst, const float *__restrict__ src, Span sp,
+                                            size_t ntiles) {
+  copy_tiles<T, U, NT>(dst, src, sp, ntiles);
+}
+
+// copy for several buffer pairs in one launch (blockIdx.y = pair): a snapshot or a rewind of every
+// survivor without a launch per replica.
+template <int T, int U, bool NT>
+__global__ __launch_bounds__(T) void k_copy_many(CopyManyArgs a, Span sp, size_t ntiles) {
+  copy_tiles<T, U, NT>(a.dst[blockIdx.y], a.src[blockIdx.y], sp, ntiles);
+}
+
 // ---------------------------------------------------------------------------------------------
 // reduce: out[i] = ((src0[i] + src1[i]) + ...) / divisor, ascending contributor order; in-place mode
 // also stores the undivided sum to every sum_dst buffer.  A workgroup walks the contributors one
-// after the other over its whole tile (U consecutive 4 KiB rows per contributor), two contributors'
+// after the other over its whole tile (U consecutive 1 KiB rows per contributor), two contributors'
 // loads in flight at a time, so each of its bursts reads one buffer contiguously; every element's
 // adds stay strictly left to right.
 // ---------------------------------------------------------------------------------------------
+// sum[u] = contributor sum of the tile's vectors, for the lanes with ok[u].
+template <int T, int U, bool NT>
+__device__ inline void contributor_sum(const ReduceArgs &a, const Span &sp, size_t base, const bool (&ok)[U],
+                                       f32x4 (&sum)[U]) {
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int u = 0; u < U; ++u) sum[u] = zero;
+  int r = 0;
+  if (a.n_src > 0) {
+    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + base;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) sum[u] = ld<NT>(s0 + size_t(T) * u);
+    r = 1;
+  }
+  for (; r + 1 < a.n_src; r += 2) {
+    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
+    const f32x4 *s1 = reinterpret_cast<const f32x4 *>(a.src[r + 1] + sp.vbegin) + base;
+    f32x4 t0[U], t1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) t0[u] = ld<NT>(s0 + size_t(T) * u);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) t1[u] = ld<NT>(s1 + size_t(T) * u);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) sum[u] = (sum[u] + t0[u]) + t1[u];
+  }
+  if (r < a.n_src) {
+    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) sum[u] = sum[u] + ld<NT>(s0 + size_t(T) * u);
+  }
+}
+
 template <int T, int U, bool NT, bool INPLACE>
 __global__ __launch_bounds__(T) void k_reduce(ReduceArgs a, Span sp, size_t ntiles) {
   f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
-  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const size_t base = tile * size_t(T * U) + threadIdx.x;
-    bool ok[U];
+    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
+      constexpr bool FULL = decltype(full)::value;
+      bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = base + size_t(T) * u < sp.nvec;
-    f32x4 sum[U];
+      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
+      f32x4 sum[U];
+      contributor_sum<T, U, NT>(a, sp, base, ok, sum);
+      if (INPLACE) {
+        for (int d = 0; d < a.n_sum_dst; ++d) {
+          f32x4 *dd = reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + base;
 #pragma unroll
-    for (int u = 0; u < U; ++u) sum[u] = zero;
-    int r = 0;
-    if (a.n_src > 0) {
-      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + base;
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) sum[u] = ld<NT>(s0 + size_t(T) * u);
-      r = 1;
-    }
-    for (; r + 1 < a.n_src; r += 2) {
-      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
-      const f32x4 *s1 = reinterpret_cast<const f32x4 *>(a.src[r + 1] + sp.vbegin) + base;
-      f32x4 t0[U], t1[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) t0[u] = ld<NT>(s0 + size_t(T) * u);
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) t1[u] = ld<NT>(s1 + size_t(T) * u);
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) sum[u] = (sum[u] + t0[u]) + t1[u];
-    }
-    if (r < a.n_src) {
-      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) sum[u] = sum[u] + ld<NT>(s0 + size_t(T) * u);
-    }
-    if (INPLACE) {
-      for (int d = 0; d < a.n_sum_dst; ++d) {
-        f32x4 *dd = reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + base;
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-          if (ok[u]) st<NT>(dd + size_t(T) * u, sum[u]);
+          for (int u = 0; u < U; ++u)
+            if (ok[u]) st<NT>(dd + size_t(T) * u, sum[u]);
+        }
       }
-    }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (ok[u]) {
-        f32x4 q;
-        q.x = sum[u].x / a.divisor;
-        q.y = sum[u].y / a.divisor;
-        q.z = sum[u].z / a.divisor;
-        q.w = sum[u].w / a.divisor;
-        st<NT>(o4 + base + size_t(T) * u, q);
+      for (int u = 0; u < U; ++u) {
+        if (ok[u]) {
+          f32x4 q;
+          q.x = sum[u].x / a.divisor;
+          q.y = sum[u].y / a.divisor;
+          q.z = sum[u].z / a.divisor;
+          q.w = sum[u].w / a.divisor;
+          st<NT>(o4 + base + size_t(T) * u, q);
+        }
       }
-    }
+    });
   }
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t i = ragged_index(sp, threadIdx.x);
@@ -284,9 +337,62 @@ __device__ inline void adam1(float &p, float &m, float &v, float g, const AdamAr
   p = __builtin_fmaf(-h.step_size, m / denom, p * h.decay_mul);
 }
 
+// Round to nearest even; a NaN stays a NaN (quiet bit set) instead of being carried into Inf or zero by
+// the rounding increment.
 __device__ inline uint32_t f32_to_bf16_rne(float x) {
   uint32_t b = __builtin_bit_cast(uint32_t, x);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (b >> 16) | 0x40u;
   return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ inline u32x2 pack_bf16x4(f32x4 p) {
+  u32x2 w;
+  w.x = f32_to_bf16_rne(p.x) | (f32_to_bf16_rne(p.y) << 16);
+  w.y = f32_to_bf16_rne(p.z) | (f32_to_bf16_rne(p.w) << 16);
+  return w;
+}
+
+// Loads p, m, v of the tile, applies the update with gradient gv, stores p, m, v (and the bf16 copy).
+template <int T, int U, bool NT, bool BF16OUT>
+__device__ inline void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restrict__ m4, f32x4 *__restrict__ v4,
+                                 u32x2 *__restrict__ b2, size_t base, const bool (&ok)[U], const f32x4 (&gv)[U],
+                                 const AdamArgs &h) {
+  f32x4 pv[U], mv[U], vv[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (ok[u]) pv[u] = ld<NT>(p4 + base + size_t(T) * u);
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (ok[u]) mv[u] = ld<NT>(m4 + base + size_t(T) * u);
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (ok[u]) vv[u] = ld<NT>(v4 + base + size_t(T) * u);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (ok[u]) {
+#pragma unroll
+      for (int l = 0; l < 4; ++l) {
+        float pp = pv[u][l], mm = mv[u][l], v1 = vv[u][l];
+        adam1(pp, mm, v1, gv[u][l], h);
+        pv[u][l] = pp;
+        mv[u][l] = mm;
+        vv[u][l] = v1;
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (ok[u]) st<NT>(p4 + base + size_t(T) * u, pv[u]);
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (ok[u]) st<NT>(m4 + base + size_t(T) * u, mv[u]);
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (ok[u]) st<NT>(v4 + base + size_t(T) * u, vv[u]);
+  if (BF16OUT) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) st<NT>(b2 + base + size_t(T) * u, pack_bf16x4(pv[u]));
+  }
 }
 
 template <int T, int U, bool NT, bool BF16OUT>
@@ -301,54 +407,17 @@ __global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__res
   u32x2 *b2 = reinterpret_cast<u32x2 *>(pb);
   for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const size_t base = tile * size_t(T * U) + threadIdx.x;
-    f32x4 gv[U], pv[U], mv[U], vv[U];
-    bool ok[U];
+    on_tile((tile + 1) * size_t(T * U) <= nvec, [&](auto full) {
+      constexpr bool FULL = decltype(full)::value;
+      bool ok[U];
+      f32x4 gv[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = base + size_t(T) * u < nvec;
-    // one buffer after the other, U consecutive rows each
+      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) gv[u] = ld<NT>(g4 + base + size_t(T) * u);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) pv[u] = ld<NT>(p4 + base + size_t(T) * u);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) mv[u] = ld<NT>(m4 + base + size_t(T) * u);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) vv[u] = ld<NT>(v4 + base + size_t(T) * u);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-#pragma unroll
-      for (int l = 0; l < 4; ++l) {
-        float pp = pv[u][l], mm = mv[u][l], v1 = vv[u][l];
-        adam1(pp, mm, v1, gv[u][l], h);
-        pv[u][l] = pp;
-        mv[u][l] = mm;
-        vv[u][l] = v1;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) st<NT>(p4 + base + size_t(T) * u, pv[u]);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) st<NT>(m4 + base + size_t(T) * u, mv[u]);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) st<NT>(v4 + base + size_t(T) * u, vv[u]);
-    if (BF16OUT) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (ok[u]) {
-          u32x2 w;
-          w.x = f32_to_bf16_rne(pv[u].x) | (f32_to_bf16_rne(pv[u].y) << 16);
-          w.y = f32_to_bf16_rne(pv[u].z) | (f32_to_bf16_rne(pv[u].w) << 16);
-          st<NT>(b2 + base + size_t(T) * u, w);
-        }
-      }
-    }
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) gv[u] = ld<NT>(g4 + base + size_t(T) * u);
+      adam_tile<T, U, NT, BF16OUT>(p4, m4, v4, b2, base, ok, gv, h);
+    });
   }
   if (blockIdx.x == 0 && threadIdx.x < 4) {
     const size_t i = nvec * 4 + threadIdx.x;
@@ -364,51 +433,41 @@ __global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__res
 }
 
 // ---------------------------------------------------------------------------------------------
-// fused reduce + AdamW: the contributor sum of k_reduce, its division, and the update of k_adamw in
-// one pass; the gradient goes to HBM only if WRITE_GRAD.  4 R_c + 24 (+4) bytes per element.
+// fused reduce + AdamW: the contributor sum of k_reduce (same walk, same order), its division, and the
+// update of k_adamw in one pass; the gradient goes to HBM only if WRITE_GRAD.  4 R_c + 24 (+4) bytes
+// per element.
 // ---------------------------------------------------------------------------------------------
-template <int T, bool NT, bool WRITE_GRAD, bool BF16OUT>
+template <int T, int U, bool NT, bool WRITE_GRAD, bool BF16OUT>
 __global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, float *__restrict__ p, float *__restrict__ m,
                                                     float *__restrict__ v, uint16_t *__restrict__ pb, Span sp,
-                                                    AdamArgs h_arg, const AdamArgs *h_dev) {
+                                                    AdamArgs h_arg, const AdamArgs *h_dev, size_t ntiles) {
   const AdamArgs h = h_dev ? *h_dev : h_arg;
-  const size_t i = size_t(blockIdx.x) * T + threadIdx.x;
-  if (i < sp.nvec) {
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    int r = 0;
-    if (a.n_src > 0) {
-      sum = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + i);
-      r = 1;
-    }
-    for (; r + 1 < a.n_src; r += 2) {
-      const f32x4 t0 = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + i);
-      const f32x4 t1 = ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r + 1] + sp.vbegin) + i);
-      sum = (sum + t0) + t1;
-    }
-    if (r < a.n_src) sum = sum + ld<NT>(reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + i);
-    f32x4 *p4 = reinterpret_cast<f32x4 *>(p + sp.vbegin) + i;
-    f32x4 *m4 = reinterpret_cast<f32x4 *>(m + sp.vbegin) + i;
-    f32x4 *v4 = reinterpret_cast<f32x4 *>(v + sp.vbegin) + i;
-    f32x4 pv = ld<NT>(p4), mv = ld<NT>(m4), vv = ld<NT>(v4), q;
+  f32x4 *p4 = reinterpret_cast<f32x4 *>(p + sp.vbegin), *m4 = reinterpret_cast<f32x4 *>(m + sp.vbegin);
+  f32x4 *v4 = reinterpret_cast<f32x4 *>(v + sp.vbegin), *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
+  u32x2 *b2 = reinterpret_cast<u32x2 *>(pb + sp.vbegin);
+  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const size_t base = tile * size_t(T * U) + threadIdx.x;
+    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
+      constexpr bool FULL = decltype(full)::value;
+      bool ok[U];
 #pragma unroll
-    for (int l = 0; l < 4; ++l) {
-      q[l] = sum[l] / a.divisor;
-      float pp = pv[l], mm = mv[l], v1 = vv[l];
-      adam1(pp, mm, v1, q[l], h);
-      pv[l] = pp;
-      mv[l] = mm;
-      vv[l] = v1;
-    }
-    st<NT>(p4, pv);
-    st<NT>(m4, mv);
-    st<NT>(v4, vv);
-    if (WRITE_GRAD) st<NT>(reinterpret_cast<f32x4 *>(a.out + sp.vbegin) + i, q);
-    if (BF16OUT) {
-      u32x2 w;
-      w.x = f32_to_bf16_rne(pv.x) | (f32_to_bf16_rne(pv.y) << 16);
-      w.y = f32_to_bf16_rne(pv.z) | (f32_to_bf16_rne(pv.w) << 16);
-      st<NT>(reinterpret_cast<u32x2 *>(pb + sp.vbegin) + i, w);
-    }
+      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
+      f32x4 sum[U];
+      contributor_sum<T, U, NT>(a, sp, base, ok, sum);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        sum[u].x = sum[u].x / a.divisor;
+        sum[u].y = sum[u].y / a.divisor;
+        sum[u].z = sum[u].z / a.divisor;
+        sum[u].w = sum[u].w / a.divisor;
+      }
+      adam_tile<T, U, NT, BF16OUT>(p4, m4, v4, b2, base, ok, sum, h);
+      if (WRITE_GRAD) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (ok[u]) st<NT>(o4 + base + size_t(T) * u, sum[u]);
+      }
+    });
   }
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t e = ragged_index(sp, threadIdx.x);
@@ -467,10 +526,13 @@ __global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, co
     cr += uint64_t(bb) * (2 * uint64_t(i) + 1);
     if (a != a || b != b) {
       nans += 1;
-    } else {
-      const uint32_t d = __builtin_bit_cast(uint32_t, __builtin_fabsf(a - b));
+    } else if (ab != bb) {  // equal bits differ by nothing (also for two equal infinities, whose difference is a NaN)
+      const uint32_t d = __builtin_bit_cast(uint32_t, __builtin_fabsf(a - b));  // +Inf for opposite infinities
       const uint32_t r = bb & 0x7FFFFFFFu;
       mdiff = d > mdiff ? d : mdiff;
+      mref = r > mref ? r : mref;
+    } else {
+      const uint32_t r = bb & 0x7FFFFFFFu;
       mref = r > mref ? r : mref;
     }
   }
@@ -504,6 +566,17 @@ static bool grid_for(size_t nvec, int T, int U, unsigned *grid, size_t *ntiles) 
   return true;
 }
 
+// Dynamic LDS bytes per workgroup that leave room for `waves` wavefronts of T-lane workgroups on a CU
+// (160 KiB of LDS each); 0 = no limit.  The kernels never touch the allocation.
+static unsigned lds_share(int waves, int T) {
+  const int per_wg = T / 64;
+  if (waves <= 0 || waves >= 32) return 0;
+  int wgs = waves / per_wg;
+  if (wgs < 1) wgs = 1;
+  unsigned b = (163840u / (unsigned)wgs) & ~255u;
+  return b > 65536u ? 65536u : b;
+}
+
 template <int V>
 using Int = std::integral_constant<int, V>;
 
@@ -533,7 +606,9 @@ hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool gra
                              size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
-  const int Uv = tuning().vecs_per_thread, Tv = tuning().threads;
+  const Shape sh = tuning().shape[grad_is_bf16 ? (first ? kAccFirstBf16 : kAccRmwBf16) : (first ? kAccFirstF32 : kAccRmwF32)];
+  const int Uv = sh.vecs, Tv = tuning().threads;
+  const unsigned lds = lds_share(sh.waves, Tv);
   unsigned grid;
   size_t ntiles;
   if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
@@ -545,7 +620,7 @@ hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool gra
     auto go = [&](auto gptr, auto is_first, auto with_snap) {
       using GT = std::remove_cv_t<std::remove_pointer_t<decltype(gptr)>>;
       hipLaunchKernelGGL((k_accumulate<GT, T, U, NT, decltype(is_first)::value, decltype(with_snap)::value>), dim3(grid),
-                         dim3(T), 0, s, acc, snap, gptr, sp, ntiles, xc);
+                         dim3(T), lds, s, acc, snap, gptr, sp, ntiles, xc);
     };
     auto pick = [&](auto gptr) {
       if (first) {
@@ -585,14 +660,33 @@ hipError_t launch_accumulate_many(const AccumulateManyArgs &a, int n_pairs, bool
 hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
-  const int Uv = tuning().copy_vecs, Tv = tuning().threads;
+  const Shape sh = tuning().shape[kCopy];
+  const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
   if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
   with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
     constexpr int T = decltype(t)::value, U = decltype(u)::value;
     constexpr bool NT = decltype(nt)::value;
-    hipLaunchKernelGGL((k_copy<T, U, NT>), dim3(grid), dim3(T), 0, s, dst, src, sp, ntiles);
+    hipLaunchKernelGGL((k_copy<T, U, NT>), dim3(grid), dim3(T), lds_share(sh.waves, T), s, dst, src, sp, ntiles);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_many(const CopyManyArgs &a, int n_pairs, size_t begin, size_t end, hipStream_t s) {
+  if (begin >= end || n_pairs <= 0) return hipSuccess;
+  if (n_pairs > kMaxReplicas) return hipErrorInvalidConfiguration;
+  const Span sp = make_span(begin, end);
+  const Shape sh = tuning().shape[kCopy];
+  const int Uv = sh.vecs, Tv = tuning().threads;
+  unsigned grid;
+  size_t ntiles;
+  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+    constexpr int T = decltype(t)::value, U = decltype(u)::value;
+    constexpr bool NT = decltype(nt)::value;
+    hipLaunchKernelGGL((k_copy_many<T, U, NT>), dim3(grid, (unsigned)n_pairs), dim3(T), lds_share(sh.waves, T), s, a, sp,
+                       ntiles);
   });
   return hipGetLastError();
 }
@@ -600,7 +694,8 @@ hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, h
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
-  const int Uv = tuning().reduce_vecs, Tv = tuning().threads;
+  const Shape sh = tuning().shape[kReduce];
+  const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
   if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
@@ -608,10 +703,11 @@ hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStrea
   with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
     constexpr int T = decltype(t)::value, U = decltype(u)::value;
     constexpr bool NT = decltype(nt)::value;
+    const unsigned lds = lds_share(sh.waves, T);
     if (inplace)
-      hipLaunchKernelGGL((k_reduce<T, U, NT, true>), dim3(grid), dim3(T), 0, s, a, sp, ntiles);
+      hipLaunchKernelGGL((k_reduce<T, U, NT, true>), dim3(grid), dim3(T), lds, s, a, sp, ntiles);
     else
-      hipLaunchKernelGGL((k_reduce<T, U, NT, false>), dim3(grid), dim3(T), 0, s, a, sp, ntiles);
+      hipLaunchKernelGGL((k_reduce<T, U, NT, false>), dim3(grid), dim3(T), lds, s, a, sp, ntiles);
   });
   return hipGetLastError();
 }
@@ -625,18 +721,20 @@ hipError_t launch_adam_prologue(StepState *st, float lr, float beta1, float beta
 hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, const AdamArgs &h,
                         const AdamArgs *device_args, hipStream_t s) {
   if (n == 0) return hipSuccess;
-  const int Uv = tuning().adamw_vecs, Tv = tuning().threads;
+  const Shape sh = tuning().shape[kAdamw];
+  const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
   size_t ntiles;
   if (!grid_for(n / 4, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
   with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
     constexpr int T = decltype(t)::value, U = decltype(u)::value;
     constexpr bool NT = decltype(nt)::value;
+    const unsigned lds = lds_share(sh.waves, T);
     if (p_bf16)
-      hipLaunchKernelGGL((k_adamw<T, U, NT, true>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, device_args,
+      hipLaunchKernelGGL((k_adamw<T, U, NT, true>), dim3(grid), dim3(T), lds, s, p, m, v, g, p_bf16, n, h, device_args,
                          ntiles);
     else
-      hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), 0, s, p, m, v, g, p_bf16, n, h, device_args,
+      hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), lds, s, p, m, v, g, p_bf16, n, h, device_args,
                          ntiles);
   });
   return hipGetLastError();
@@ -647,23 +745,26 @@ hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v
                                hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
-  const size_t tiles = (sp.nvec + 63) / 64;  // one tile per one-wavefront workgroup, no grid cap
-  if (tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  const unsigned grid = tiles ? (unsigned)tiles : 1u;
-  auto go = [&](auto nt, auto wg, auto bf) {
-    hipLaunchKernelGGL((k_reduce_adamw<64, decltype(nt)::value, decltype(wg)::value, decltype(bf)::value>), dim3(grid),
-                       dim3(64), 0, s, a, p, m, v, p_bf16, sp, h, device_args);
-  };
-  auto with_bf = [&](auto nt, auto wg) {
-    if (p_bf16) go(nt, wg, std::true_type{});
-    else go(nt, wg, std::false_type{});
-  };
-  auto with_wg = [&](auto nt) {
-    if (write_grad) with_bf(nt, std::true_type{});
-    else with_bf(nt, std::false_type{});
-  };
-  if (tuning().nontemporal) with_wg(std::true_type{});
-  else with_wg(std::false_type{});
+  const Shape sh = tuning().shape[kReduceAdamw];
+  const int Uv = sh.vecs, Tv = tuning().threads;
+  unsigned grid;
+  size_t ntiles;
+  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+    constexpr int T = decltype(t)::value, U = decltype(u)::value;
+    constexpr bool NT = decltype(nt)::value;
+    const unsigned lds = lds_share(sh.waves, T);
+    auto go = [&](auto wg, auto bf) {
+      hipLaunchKernelGGL((k_reduce_adamw<T, U, NT, decltype(wg)::value, decltype(bf)::value>), dim3(grid), dim3(T), lds,
+                         s, a, p, m, v, p_bf16, sp, h, device_args, ntiles);
+    };
+    auto with_bf = [&](auto wg) {
+      if (p_bf16) go(wg, std::true_type{});
+      else go(wg, std::false_type{});
+    };
+    if (write_grad) with_bf(std::true_type{});
+    else with_bf(std::false_type{});
+  });
   return hipGetLastError();
 }
 

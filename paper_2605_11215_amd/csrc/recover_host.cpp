@@ -15,6 +15,7 @@
 #include "kernels.h"
 
 using recover::kMaxReplicas;
+static_assert(RECOVER_KERNEL_CLASSES == recover::kNumClasses, "kernel classes of the header and of the launchers must agree");
 
 struct recover_ctx {
   int W = 0, G = 0, B = 0, T = 0;
@@ -235,7 +236,7 @@ int recover_init(const recover_config *cfg, recover_ctx **out) {
   c->host_only = host_only;
   c->adaptive = cfg->flags & RECOVER_FLAG_ADAPTIVE;
   c->any_order = cfg->flags & RECOVER_FLAG_ANY_ORDER;
-  c->have_snap = host_only ? true : cfg->snap != nullptr;
+  c->have_snap = cfg->snap != nullptr;  // host-only: the array's entries may be NULL, its presence counts
   if (!host_only) {
     for (int r = 0; r < c->W; ++r) {
       c->acc[r] = cfg->acc[r];
@@ -416,12 +417,21 @@ int recover_snapshot(recover_ctx *c, int replica, int tb, int te, void *stream) 
         return fail(c, RECOVER_ERR_STATE, "snapshot: tensor %d of replica %d already holds a reduced sum", b, r);
   }
   if (int e = order_after_previous(c, (hipStream_t)stream, "snapshot")) return e;
+  recover::CopyManyArgs a;
+  int n = 0;
   for (int r = 0; r < c->W; ++r) {
     if ((replica >= 0 && r != replica) || !alive(c, r)) continue;
-    if (!c->host_only) {
-      hipError_t he = recover::launch_copy(c->snap[r], c->acc[r], (size_t)c->off[tb], (size_t)c->off[te], (hipStream_t)stream);
-      if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "snapshot: %s", hipGetErrorString(he));
-    }
+    a.dst[n] = c->snap[r];
+    a.src[n] = c->acc[r];
+    ++n;
+  }
+  if (!c->host_only) {  // one launch whatever the number of replicas
+    hipError_t he = n == 1 ? recover::launch_copy(a.dst[0], a.src[0], (size_t)c->off[tb], (size_t)c->off[te], (hipStream_t)stream)
+                           : recover::launch_copy_many(a, n, (size_t)c->off[tb], (size_t)c->off[te], (hipStream_t)stream);
+    if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "snapshot: %s", hipGetErrorString(he));
+  }
+  for (int r = 0; r < c->W; ++r) {
+    if ((replica >= 0 && r != replica) || !alive(c, r)) continue;
     for (int b = tb; b < te; ++b) {
       const size_t i = (size_t)r * c->T + b;
       c->snap_valid[i] = 1;
@@ -435,8 +445,21 @@ int recover_snapshot(recover_ctx *c, int replica, int tb, int te, void *stream) 
 int recover_restore(recover_ctx *c, int replica, int stale_only, void *stream) {
   if (!c) return RECOVER_ERR_ARG;
   if (replica < -1 || replica >= c->W) return fail(c, RECOVER_ERR_ARG, "restore: replica %d out of range", replica);
-  if (!c->have_snap) return fail(c, RECOVER_ERR_NO_SNAPSHOT, "restore: context has no snapshot buffers");
   if (replica >= 0 && !alive(c, replica)) return fail(c, RECOVER_ERR_STATE, "restore: replica %d is dead", replica);
+  if (!c->have_snap) {
+    // Without snapshot buffers no bucket was ever snapshotted, so the stale set of Alg. 5 is empty (SKIP):
+    // nothing is copied and the quiesce is lifted.  Only a bucket that holds an in-place sum of the old
+    // membership cannot be repaired then.
+    for (int r = 0; r < c->W; ++r) {
+      if ((replica >= 0 && r != replica) || !alive(c, r)) continue;
+      for (int b = 0; b < c->T; ++b)
+        if (c->holds_sum[(size_t)r * c->T + b])
+          return fail(c, RECOVER_ERR_NO_SNAPSHOT, "restore: tensor %d of replica %d holds a reduced sum and the context has no snapshot buffers", b, r);
+    }
+    c->quiesced = false;
+    if (replica < 0) c->restore_mode = RECOVER_RESTORE_SKIP;
+    return RECOVER_OK;
+  }
   // plan first: which tensors rewind, and whether each replica ends on one microbatch count
   std::vector<uint8_t> pick((size_t)c->W * c->T, 0);
   for (int r = 0; r < c->W; ++r) {
@@ -456,30 +479,48 @@ int recover_restore(recover_ctx *c, int replica, int stale_only, void *stream) {
       return fail(c, RECOVER_ERR_STATE, "restore: rewind would leave replica %d between microbatches", r);
   }
   if (int e = order_after_previous(c, (hipStream_t)stream, "restore")) return e;
+  // Device work first.  Replicas that rewind the same set of tensors (the usual case: the buckets that were
+  // all-reduced before the failure showed) share one launch per run of adjacent tensors.
+  if (!c->host_only) {
+    std::vector<uint8_t> done(c->W, 0);
+    for (int r0 = 0; r0 < c->W; ++r0) {
+      if (done[r0] || (replica >= 0 && r0 != replica) || !alive(c, r0)) continue;
+      recover::CopyManyArgs a;
+      int n = 0;
+      for (int r = r0; r < c->W; ++r) {
+        if (done[r] || (replica >= 0 && r != replica) || !alive(c, r)) continue;
+        if (memcmp(&pick[(size_t)r * c->T], &pick[(size_t)r0 * c->T], (size_t)c->T) != 0) continue;
+        done[r] = 1;
+        a.dst[n] = c->acc[r];
+        a.src[n] = c->snap[r];
+        ++n;
+      }
+      const uint8_t *pk = &pick[(size_t)r0 * c->T];
+      for (int b = 0; b < c->T;) {
+        if (!pk[b]) {
+          ++b;
+          continue;
+        }
+        int e = b;
+        while (e < c->T && pk[e]) ++e;
+        hipError_t he = n == 1 ? recover::launch_copy(a.dst[0], a.src[0], (size_t)c->off[b], (size_t)c->off[e], (hipStream_t)stream)
+                               : recover::launch_copy_many(a, n, (size_t)c->off[b], (size_t)c->off[e], (hipStream_t)stream);
+        if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "restore: %s", hipGetErrorString(he));
+        b = e;
+      }
+    }
+  }
   for (int r = 0; r < c->W; ++r) {
     if ((replica >= 0 && r != replica) || !alive(c, r)) continue;
     bool any = false;
-    for (int b = 0; b < c->T;) {
-      const size_t i = (size_t)r * c->T + b;
-      if (!pick[i]) {
-        ++b;
-        continue;
-      }
-      int e = b;  // one launch per run of adjacent tensors
-      while (e < c->T && pick[(size_t)r * c->T + e]) ++e;
-      if (!c->host_only) {
-        hipError_t he = recover::launch_copy(c->acc[r], c->snap[r], (size_t)c->off[b], (size_t)c->off[e], (hipStream_t)stream);
-        if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "restore: %s", hipGetErrorString(he));
-      }
-      for (int q = b; q < e; ++q) {
-        const size_t j = (size_t)r * c->T + q;
-        c->cnt[j] = c->snap_cnt[j];
-        c->holds_sum[j] = 0;
-        c->snap_eps[j] = c->eps;
-        c->red_dirty[q] = 1;
-      }
+    for (int q = 0; q < c->T; ++q) {
+      const size_t j = (size_t)r * c->T + q;
+      if (!pick[j]) continue;
+      c->cnt[j] = c->snap_cnt[j];
+      c->holds_sum[j] = 0;
+      c->snap_eps[j] = c->eps;
+      c->red_dirty[q] = 1;
       any = true;
-      b = e;
     }
     if (any) {
       const int done = c->cnt[(size_t)r * c->T];
@@ -819,33 +860,53 @@ int recover_compare(const float *x, const float *ref, int64_t n, recover_compare
 
 int recover_set_tuning(int key, int value) {
   recover::Tuning &t = recover::tuning();
+  if (key >= RECOVER_TUNE_VECS && key < RECOVER_TUNE_VECS + RECOVER_KERNEL_CLASSES) {
+    if (value != 1 && value != 2 && value != 4) return RECOVER_ERR_ARG;
+    t.shape[key - RECOVER_TUNE_VECS].vecs = value;
+    return RECOVER_OK;
+  }
+  if (key >= RECOVER_TUNE_WAVES && key < RECOVER_TUNE_WAVES + RECOVER_KERNEL_CLASSES) {
+    if (value != 0 && (value < 2 || value > 32)) return RECOVER_ERR_ARG;
+    t.shape[key - RECOVER_TUNE_WAVES].waves = value;
+    return RECOVER_OK;
+  }
   switch (key) {
-    case 7:
+    case RECOVER_TUNE_THREADS:
       if (value != 64 && value != 256) return RECOVER_ERR_ARG;
       t.threads = value;
       return RECOVER_OK;
-    case 0:
-      if (value != 1 && value != 2 && value != 4) return RECOVER_ERR_ARG;
-      t.vecs_per_thread = value;
-      return RECOVER_OK;
-    case 1:
+    case RECOVER_TUNE_NONTEMPORAL:
       if (value != 0 && value != 1) return RECOVER_ERR_ARG;
       t.nontemporal = value;
       return RECOVER_OK;
-    case 2:
+    case RECOVER_TUNE_GRID_CAP:
       if (value < 0 || value > (1 << 24)) return RECOVER_ERR_ARG;
       t.grid_cap = value;
       return RECOVER_OK;
-    case 6:
+    case RECOVER_TUNE_XCD_CHUNKED:
       if (value != 0 && value != 1) return RECOVER_ERR_ARG;
       t.xcd_chunked = value;
       return RECOVER_OK;
-    case 3:
-    case 4:
-    case 5:
-      if (value != 1 && value != 2 && value != 4) return RECOVER_ERR_ARG;
-      (key == 3 ? t.reduce_vecs : key == 4 ? t.adamw_vecs : t.copy_vecs) = value;
-      return RECOVER_OK;
+  }
+  return RECOVER_ERR_ARG;
+}
+
+int recover_get_tuning(int key, int *value) {
+  const recover::Tuning &t = recover::tuning();
+  if (!value) return RECOVER_ERR_ARG;
+  if (key >= RECOVER_TUNE_VECS && key < RECOVER_TUNE_VECS + RECOVER_KERNEL_CLASSES) {
+    *value = t.shape[key - RECOVER_TUNE_VECS].vecs;
+    return RECOVER_OK;
+  }
+  if (key >= RECOVER_TUNE_WAVES && key < RECOVER_TUNE_WAVES + RECOVER_KERNEL_CLASSES) {
+    *value = t.shape[key - RECOVER_TUNE_WAVES].waves;
+    return RECOVER_OK;
+  }
+  switch (key) {
+    case RECOVER_TUNE_THREADS: *value = t.threads; return RECOVER_OK;
+    case RECOVER_TUNE_NONTEMPORAL: *value = t.nontemporal; return RECOVER_OK;
+    case RECOVER_TUNE_GRID_CAP: *value = t.grid_cap; return RECOVER_OK;
+    case RECOVER_TUNE_XCD_CHUNKED: *value = t.xcd_chunked; return RECOVER_OK;
   }
   return RECOVER_ERR_ARG;
 }

@@ -1,9 +1,8 @@
-"""The caller's side of Alg. 1: the microbatch loop of a training step with the forward/backward
-pass replaced by a gradient source.  It drives any engine with the method names of
-`binding.Shard` (the HIP library's context; the tests also drive the CPU oracle's `Proto`
-with it) through whole iterations.  It stands in for the training loop: it decides nothing
-the method decides; quotas, roles, loop bound and restore mode are read back from the
-engine after every call.
+"""The caller's side of Alg. 1 for the HIP library: the microbatch loop of a training step with the
+forward/backward pass replaced by a gradient source.  It drives a `binding.Shard` (or any object
+with its method names) through whole iterations and stands in for the training loop: it decides
+nothing the method decides; quotas, roles, loop bound and restore mode are read back from the
+context after every call.  The benchmark's failure iteration and the attrition report use it.
 
 Microbatch ids: replica r's k-th microbatch of an iteration has global id r + W_init * k
 (each replica advances through its own slice of the stream; a failed replica's slice drops
@@ -11,13 +10,6 @@ out), so a failure-free iteration commits ids 0 .. B-1 and extra microbatches ge
 """
 
 HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
-
-
-def view_oracle(p):
-    """State view of an object that keeps its bookkeeping in a `.world` attribute."""
-    w = p.world
-    return dict(alive=w.alive(), target=list(w.target), contributed=list(w.contributed),
-                loop_bound=w.loop_bound, role=list(w.role), epoch=w.eps)
 
 
 def view_shard(s):

@@ -155,9 +155,12 @@ def fill(n, seed, tag, mb_id, it, scale, kind=KIND_NORMAL, start=0, chunk=1 << 2
 
 
 def f32_to_bf16_bits(x):
-    """Round-to-nearest-even bf16 bit patterns (uint16) of finite fp32 values."""
-    b = np.asarray(x, np.float32).view(np.uint32)
+    """Round-to-nearest-even bf16 bit patterns (uint16) of fp32 values; a NaN keeps its sign and upper
+    payload bits and gets the quiet bit, so it stays a NaN."""
+    b = np.ascontiguousarray(x, np.float32).view(np.uint32)
     r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    nan = (b & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+    r = np.where(nan, (b >> np.uint32(16)) | np.uint32(0x40), r)
     return r.astype(np.uint16)
 
 

@@ -112,6 +112,7 @@ __device__ inline void four_normals(const Words &w, double z[4]) {
 
 __device__ inline uint16_t bf16_rne(float x) {
   const uint32_t b = __builtin_bit_cast(uint32_t, x);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((b >> 16) | 0x40u);  // a NaN stays a NaN
   return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
 }
 

@@ -60,7 +60,15 @@ def test_argument_errors():
     assert B.recover_adamw_step(s.ctx, 1e-3, 1.5, 0.95, 1e-8, 0.1) == B.ERR_ARG
     assert B.recover_policy_adjust(s.ctx, [0, 1], 2)[0] == B.ERR_NO_SURVIVOR
     assert B.recover_policy_adjust(s.ctx, [5], 2)[0] == B.ERR_ARG
-    assert B.recover_set_tuning(0, 3) == B.ERR_ARG and B.recover_set_tuning(0, 4) == B.OK
+    key = B.TUNE_VECS + B.KERNEL_ADAMW
+    before = B.recover_get_tuning(key)
+    assert before[0] == B.OK
+    assert B.recover_set_tuning(key, 3) == B.ERR_ARG and B.recover_get_tuning(key) == before
+    assert B.recover_set_tuning(key, 4) == B.OK and B.recover_get_tuning(key) == (B.OK, 4)
+    assert B.recover_set_tuning(key, before[1]) == B.OK
+    assert B.recover_set_tuning(B.TUNE_WAVES + B.KERNEL_CLASSES, 8) == B.ERR_ARG        # no such kernel class
+    assert B.recover_set_tuning(B.TUNE_WAVES + B.KERNEL_COPY, 1) == B.ERR_ARG
+    assert B.recover_set_tuning(0, 1) == B.ERR_ARG
     assert B.recover_query(s.ctx, 2)[1]["target"] == [2, 2]        # unchanged by the failed calls
 
 
@@ -335,3 +343,45 @@ def test_snapshot_taken_between_commit_and_advancement_survives_the_advancement(
     with pytest.raises(ProtocolError):
         o.restore(0, stale_only=False)
     assert B.recover_restore(s.ctx, 0, 0) == B.ERR_STATE
+
+
+def test_context_without_snapshot_buffers_gets_past_a_failure():
+    """A context created without snapshot buffers has never snapshotted anything, so after a failure the
+    stale set of Alg. 5 is empty: the rewind only lifts the quiesce and the iteration goes on.  Only an
+    in-place sum of the old membership cannot be taken back."""
+    off = [0, 4, 8]
+    s = B.Shard(4, 2, off, host_only=True, snapshots=False)
+    o = Proto(4, 2, off, dtype=np.float32)
+    o.set_state(np.zeros(8, np.float32))
+    g = np.ones(8, np.float32)
+    for eng in (s, o):
+        for r in range(4):
+            assert eng.accumulate(r, r, g)
+        for r in (0, 1, 3):                              # replica 2 is gone after one microbatch
+            assert eng.accumulate(r, r + 4, g)
+    assert B.recover_snapshot(s.ctx, -1, 0, 2) == B.ERR_NO_SNAPSHOT
+    assert B.recover_accumulate_snapshot(s.ctx, 0, 99, 0, B.F32, 0, 2) == B.ERR_NO_SNAPSHOT
+    a, b = o.on_failure([2]), s.on_failure([2])
+    for k in INT_KEYS:
+        assert a[k] == b[k], k
+    assert b["at_boundary"] == 1 and b["restore_mode"] == B.RESTORE_NONBLOCKING
+    assert s.reduce() is False                            # quiesced
+    assert B.recover_adamw_step(s.ctx, 1e-3, 0.9, 0.95, 1e-8, 0.1) == B.ERR_STATE
+    assert o.restore(None) == 0
+    s.restore(None)                                       # no error: nothing to rewind
+    assert s.query()["restore_mode"] == B.RESTORE_SKIP
+    for eng in (s, o):
+        for r in (0, 1):
+            assert eng.accumulate(r, r + 8, g)            # the extended pass: quotas 3, 3, 2
+        assert not eng.accumulate(3, 3 + 8, g)
+        eng.reduce()
+        eng.adamw_step(**HP)
+    assert s.advance()["G_cur"] == o.advance()["G_cur"] == 3
+    # a bucket that already holds the old membership's in-place sum cannot be repaired without a snapshot
+    for r in (0, 1, 3):
+        assert s.accumulate(r, r, g)
+    s.reduce(0, 1, inplace=True)
+    s.on_failure([3])
+    assert B.recover_restore(s.ctx, -1, 1) == B.ERR_NO_SNAPSHOT
+    assert B.recover_restore(s.ctx, 3, 1) == B.ERR_STATE   # dead replica
+    s.close()

@@ -206,25 +206,38 @@ def test_negative_zero_and_stale_buffers():
 
 
 def test_launch_shapes_do_not_change_the_bits():
+    """Vectors per lane, resident wavefronts per CU, lanes per workgroup, cache hints, grid cap and tile
+    order of every kernel class: the results are the same bits under all of them, through the separate
+    and through the one-pass calls."""
     torch = torch_()
     N = OFF[-1]
     g = grads_np(11, N, 1e-3, False)
     ref = None
+    keys = [B.TUNE_NONTEMPORAL, B.TUNE_GRID_CAP, B.TUNE_XCD_CHUNKED, B.TUNE_THREADS] + \
+           [B.TUNE_VECS + k for k in range(B.KERNEL_CLASSES)] + [B.TUNE_WAVES + k for k in range(B.KERNEL_CLASSES)]
+    defaults = {k: B.recover_get_tuning(k) for k in keys}
+    assert all(code == 0 for code, _ in defaults.values())
     try:
-        for U in (1, 2, 4):
+        for U, waves in ((1, 0), (2, 8), (4, 2), (1, 32), (2, 13)):
             for nt, cap, xcd, T in ((1, 0, 1, 64), (0, 0, 0, 256), (1, 3, 0, 64), (0, 2, 1, 256)):
-                for key, val in ((0, U), (3, U), (4, U), (5, U), (1, nt), (2, cap), (6, xcd), (7, T)):
+                for key, val in ((B.TUNE_NONTEMPORAL, nt), (B.TUNE_GRID_CAP, cap), (B.TUNE_XCD_CHUNKED, xcd),
+                                 (B.TUNE_THREADS, T)):
                     assert B.recover_set_tuning(key, val) == 0
-                _, s, eng = make_pair(4, 2, OFF, False, seed=11)
-                run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={1: 1}, fidelity_k=2)
-                cur = [x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)]
-                if ref is None:
-                    ref = cur
-                for x, y in zip(ref, cur):
-                    assert torch.equal(x, y), (U, nt, cap, xcd, T)
+                for k in range(B.KERNEL_CLASSES):
+                    assert B.recover_set_tuning(B.TUNE_VECS + k, U) == 0
+                    assert B.recover_set_tuning(B.TUNE_WAVES + k, waves) == 0
+                for fuse in (False, True):
+                    _, s, eng = make_pair(4, 2, OFF, False, seed=11)
+                    run_iteration(eng, view_hip, 0, g, 4, hp=hp32(), dying={1: 1}, fidelity_k=2, fuse=fuse,
+                                  snapshot_every=fuse)
+                    cur = [x.clone() for x in (s.grad_out, s.param, s.exp_avg, s.exp_avg_sq)]
+                    if ref is None:
+                        ref = cur
+                    for x, y in zip(ref, cur):
+                        assert torch.equal(x, y), (U, waves, nt, cap, xcd, T, fuse)
     finally:
-        for key, val in ((0, 1), (1, 1), (2, 0), (3, 1), (4, 1), (5, 1), (6, 0), (7, 64)):      # the defaults
-            B.recover_set_tuning(key, val)
+        for k, (_, v) in defaults.items():
+            assert B.recover_set_tuning(k, v) == 0
 
 
 def test_promoted_spare_and_inplace_sum_on_gpu():

@@ -58,8 +58,7 @@ def test_iteration_gradient_is_the_mean_over_committed_ids(dtype, tol):
     g = grads(3)
     for t, dying in enumerate([None, {2: 1}, None, {0: 0, 3: 2}]):
         captured = {}
-        out = run_iteration(p, view_oracle, t, g, 4, dying=dying,
-                            on_sync=lambda e: None)
+        out = run_iteration(p, view_oracle, t, g, 4, dying=dying)
         ids = sum(out["ids"].values(), [])
         assert len(ids) == 8 == len(set(ids))
         want = brute.exact_mean([g(t, j) for j in ids], 8)
