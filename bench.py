@@ -1,18 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the gradient path on one MI355X.
 
-A step is one failure-free iteration of the GPT-2-small-sized shard (8 replicas, 32
-microbatches, fp32 gradients, 148 tensors, 123,589,632 elements) through the C ABI:
-32 x recover_accumulate, recover_reduce, recover_adamw_step, recover_policy_adjust.
-Gradients are synthetic (seeded Philox streams), pre-generated into a pool of four HBM
-buffers before the timed region: generating them stands in for the backward pass.
+A step is one failure-free iteration of a workload through the C ABI: M x recover_accumulate,
+recover_reduce, recover_adamw_step, recover_policy_adjust.  The headline workload (default) is the
+largest single-GPU configuration, configs[4]: the Llama-70B-like 1/16 shard, 1,978,662,912 elements
+in 259 tensors, bf16 gradients accumulated in fp32, R = 4 replicas, M = 16 microbatches per iteration.
+Gradients are synthetic (seeded Philox streams), pre-generated into a pool of four HBM buffers before
+the timed region: generating them stands in for the backward pass.
 
-Prints ONE JSON line: effective HBM GB/s = algorithmic bytes per iteration / time, with a
-`roofline` object for the dominant kernel (the read-modify-write accumulate, timed with
-events on the launch stream inside the timed region) and a `cpu_baseline` object (the CPU
-oracle, as it stands, on a bounded slice of the same workload).  Extra keys, each timed
-separately after the headline region: every kernel's rate, the iteration with a snapshot of every
-replica, the one-pass variants, the non-blocking rewind, and one whole failure iteration.
+Prints ONE JSON line: effective HBM GB/s = algorithmic bytes per iteration / time, with
+  roofline      the dominant kernel (the read-modify-write accumulate), timed with events on the launch
+                stream inside the timed region
+  cpu_baseline  the CPU oracle, as it stands, on a bounded slice of the same workload
+  per_config    the other workloads (configs[1], [2], [3]), each timed the same way on a fresh context
+                after the headline's buffers are freed, each with its own roofline block
+and, timed separately after the headline region: every kernel's rate, snapshot and restore alone, the
+one-pass variants, the non-blocking rewind, one whole failure iteration, and the read-only / copy
+ceilings of this chip measured with the library's own kernels.
 """
 import argparse
 import json
@@ -26,21 +30,22 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
 POOL = 4
-
+# Arithmetic type of the path: accumulators, contributor sum, the division and AdamW are all fp32 (bf16 is
+# only the storage type of the incoming microbatch gradients of configs[2] and configs[4]).
+ARITHMETIC = "f32"
+SLAB = {"on": True, "pad": 4 << 20}          # buffer placement, see binding.alloc_slab
 
 WORKLOAD_TEXT = {
     1: "configs[0] tiny: 1,048,576 fp32 elements, R=4, M=8 (cache- and launch-bound, not an HBM measurement)",
     2: "configs[1] GPT-2-small-sized shard: 123,589,632 fp32 elements in 148 tensors, R=8 replicas, "
        "M=32 microbatches/iteration, failure-free iteration",
-    3: "configs[2] Llama-3-8B 1/8 HSDP shard: 1,003,749,376 elements in 30 tensors, bf16 gradients, R=8, M=64",
-    4: "configs[3] heavy attrition shape: 100,663,296 fp32 elements in 12 tensors, R=64, M=128",
-    5: "configs[4] Llama-70B-like 1/16 shard: 1,978,662,912 elements in 259 tensors, bf16 gradients, R=4, M=16",
+    3: "configs[2] Llama-3-8B 1/8 HSDP shard: 1,003,749,376 elements in 30 tensors, bf16 gradients accumulated in "
+       "fp32, R=8, M=64, failure-free iteration",
+    4: "configs[3] heavy attrition shape: 100,663,296 fp32 elements in 12 tensors, R=64, M=128, failure-free iteration",
+    5: "configs[4] Llama-70B-like 1/16 shard: 1,978,662,912 elements in 259 tensors, bf16 gradients accumulated in "
+       "fp32, R=4 replicas, M=16 microbatches/iteration, failure-free iteration",
 }
-
-
-def workload(k=2):
-    from paper_2605_11215_amd.workloads import CONFIGS
-    return CONFIGS[k]
+TRAFFIC_FILE = {5: "accumulate_bf16_llama70b_split16_shard_pmc.txt", 2: "accumulate_f32_gpt2_shard_pmc.txt"}
 
 
 def bytes_per_elem(W, M, s_g, R_c):
@@ -51,11 +56,14 @@ def bytes_per_elem(W, M, s_g, R_c):
     return dict(accumulate=acc, reduce=4 * R_c + 4, adamw=28, total=acc + 4 * R_c + 4 + 28)
 
 
-def read_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary."""
-    path = os.path.join(ROOT, "profiles", "accumulate_f32_gpt2_shard_pmc.txt")
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary of this
+    benchmark command (counters cannot be read from inside the run)."""
+    name = TRAFFIC_FILE.get(workload)
+    if not name:
+        return None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
                 return float(line.split("=")[1])
     except OSError:
@@ -63,9 +71,15 @@ def read_traffic():
     return None
 
 
+def quantiles(xs):
+    xs = sorted(xs)
+    pick = lambda q: xs[min(len(xs) - 1, int(round(q * (len(xs) - 1))))]
+    return dict(mean=sum(xs) / len(xs), median=pick(0.5), p10=pick(0.1), p90=pick(0.9), n=len(xs))
+
+
 def cpu_baseline(c, pool_slices, iters):
     """The oracle's fp32 protocol simulator on a contiguous slice: `iters` failure-free
-    iterations (32 accumulates, reduce, AdamW).  Only this leg touches oracle/."""
+    iterations (M accumulates, reduce, AdamW).  Only this leg touches oracle/."""
     import numpy as np
     from oracle.proto import Proto
     n = len(pool_slices[0])
@@ -88,59 +102,48 @@ def cpu_baseline(c, pool_slices, iters):
                 seconds=dt, host_cpus=os.cpu_count())
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-slice", type=int, default=1 << 24)
-    ap.add_argument("--cpu-iters", type=int, default=16)
-    ap.add_argument("--settle-seconds", type=float, default=15.0,
-                    help="upper bound of the untimed settling phase before the warmup (see settle())")
-    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5],
-                    help="which of the five configs to time (default 2 = the headline workload, configs[1])")
-    ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
-    a = ap.parse_args()
-    if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's HBM); "
-              "--gpus %d is not supported" % a.gpus, file=sys.stderr)
-        sys.exit(2)
+class Leg:
+    """One workload resident in HBM: context, gradient pool, and the timed iteration."""
 
-    import torch
-    from paper_2605_11215_amd import binding as B
-    from paper_2605_11215_amd import synth
-    from paper_2605_11215_amd.synth import reference_np as S
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; this library has no CPU path", file=sys.stderr)
-        sys.exit(3)
-    B.lib()
-    for kv in filter(None, a.tuning.split(",")):
-        k, v = kv.split("=")
-        assert B.recover_set_tuning(int(k), int(v)) == 0, kv
+    def __init__(self, k):
+        import torch
+        from paper_2605_11215_amd import binding as B
+        from paper_2605_11215_amd import synth
+        from paper_2605_11215_amd.synth import reference_np as S
+        from paper_2605_11215_amd.workloads import CONFIGS
+        self.torch, self.B, self.synth, self.S = torch, B, synth, S
+        self.k, self.c = k, CONFIGS[k]
+        c = self.c
+        self.s_g = 2 if c["bf16"] else 4
+        self.W, self.G, self.off = c["W"], c["G"], c["off"]
+        self.N, self.M, self.T = self.off[-1], c["W"] * c["G"], len(self.off) - 1
+        gdt, self.gcode = (torch.bfloat16, B.BF16) if c["bf16"] else (torch.float32, B.F32)
+        self.sh = B.Shard(self.W, self.G, self.off, device="cuda:0", snapshots=True, slab=SLAB["on"],
+                          slab_pad=SLAB["pad"], extra=[(gdt, self.N)] * POOL)
+        synth.fill_device(self.sh.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=self.N)
+        self.pool = [synth.fill_device(g, c["seed"], S.TAG_GRAD, j, 0, c["scale"], c["kind"])
+                     for j, g in enumerate(self.sh.extra)]
+        self.gptr = [g.data_ptr() for g in self.pool]
+        torch.cuda.synchronize()
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.ctx = self.sh.ctx
+        self.bpe = bytes_per_elem(self.W, self.M, self.s_g, self.W)
 
-    c = workload(a.workload)
-    s_g = 2 if c["bf16"] else 4
-    W, G, off = c["W"], c["G"], c["off"]
-    N, M = off[-1], c["W"] * c["G"]
-    T = len(off) - 1
-    torch.cuda.set_device(0)
-    sh = B.Shard(W, G, off, device="cuda:0", snapshots=True)
-    synth.fill_device(sh.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=N)
-    gdt, gcode = (torch.bfloat16, B.BF16) if c["bf16"] else (torch.float32, B.F32)
-    pool = [synth.fill_device(torch.empty(N, dtype=gdt, device="cuda:0"), c["seed"], S.TAG_GRAD, j, 0,
-                              c["scale"], c["kind"]) for j in range(POOL)]
-    gptr = [g.data_ptr() for g in pool]
-    torch.cuda.synchronize()
-    stream = torch.cuda.current_stream().cuda_stream
-    ctx = sh.ctx
-    ev = lambda: torch.cuda.Event(enable_timing=True)
+    def close(self):
+        self.sh.close()
+        self.sh = self.pool = None
+        self.torch.cuda.synchronize()
+        self.torch.cuda.empty_cache()
 
-    def iteration(marks=None, snapshot=False, fused=False, snapshot_every=False):
-        """One failure-free iteration.  marks: list receiving event pairs per phase.  fused: the one-pass
+    def ev(self):
+        return self.torch.cuda.Event(enable_timing=True)
+
+    def iteration(self, marks=None, snapshot=False, fused=False, snapshot_every=False):
+        """One failure-free iteration.  marks: list receiving the event list of the phases.  fused: the one-pass
         reduce+AdamW call; snapshot_every: the one-pass accumulate+snapshot call for every microbatch."""
+        B, ctx, W, G, T, stream, gptr, gcode = self.B, self.ctx, self.W, self.G, self.T, self.stream, self.gptr, self.gcode
         acc_call = B.recover_accumulate_snapshot if snapshot_every else B.recover_accumulate
-        e = [ev() for _ in range(5)] if marks is not None else None
+        e = [self.ev() for _ in range(5)] if marks is not None else None
         if e:
             e[0].record()
         for r in range(W):                                    # k = 0: overwrite variant
@@ -171,18 +174,18 @@ def main():
         rc, _ = B.recover_policy_adjust(ctx, [], W)
         assert rc == 0
 
-    def settle(limit_s):
+    def settle(self, limit_s):
         """Untimed: repeat iterations until three successive windows agree to 0.7 % (or the time limit).
-        Memory that a previous process freed is wiped by the driver in the background and takes HBM
-        bandwidth while it lasts (measured: 2 % for ~8 s after a process that held 200 GB), so a run
-        started right after another GPU job would otherwise time that, not this path."""
+        Memory that a previous process (or the previous leg) freed is wiped by the driver in the background
+        and takes HBM bandwidth while it lasts, so a run started right after would otherwise time that."""
+        torch = self.torch
         t_start, windows = time.perf_counter(), []
-        n_win = max(5, int(0.2 / max(1e-4, 416 * N / 6e12)))         # about 0.2 s per window
+        n_win = max(2, int(0.2 / max(1e-4, self.bpe["total"] * self.N / 6e12)))         # about 0.2 s per window
         while time.perf_counter() - t_start < limit_s:
             torch.cuda.synchronize()
             t_w = time.perf_counter()
             for _ in range(n_win):
-                iteration()
+                self.iteration()
             torch.cuda.synchronize()
             windows.append((time.perf_counter() - t_w) / n_win)
             last = windows[-3:]
@@ -190,187 +193,289 @@ def main():
                 break
         return time.perf_counter() - t_start, len(windows)
 
-    settle_s, settle_windows = settle(a.settle_seconds) if a.settle_seconds > 0 else (0.0, 0)
-    for _ in range(a.warmup):
-        iteration()
-    torch.cuda.synchronize()
-    marks = []
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        iteration(marks)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms = dt * 1e3 / a.steps
-
-    bpe = bytes_per_elem(W, M, s_g, W)
-    gbs = bpe["total"] * N / (dt / a.steps) / 1e9
-    phase = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]     # ms per iteration
-    n_rmw = (G - 1) * W
-    rmw_ms = phase[1] / n_rmw
-    k_gbs = dict(accumulate_first=W * (s_g + 4) * N / phase[0] / 1e6, accumulate_rmw=(s_g + 8) * N / rmw_ms / 1e6,
-                 reduce=bpe["reduce"] * N / phase[2] / 1e6, adamw=28 * N / phase[3] / 1e6)
-
-    # the same iteration with a snapshot of every replica before the reduction (Alg. 1, snapshot step)
-    for _ in range(2):
-        iteration(snapshot=True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ns = max(5, a.steps // 5)
-    for _ in range(ns):
-        iteration(snapshot=True)
-    torch.cuda.synchronize()
-    dts = (time.perf_counter() - t1) / ns
-    with_snapshot = dict(ms_per_step=dts * 1e3, bytes_per_elem=bpe["total"] + 8 * W,
-                         GBps=(bpe["total"] + 8 * W) * N / dts / 1e9)
-
-    def timed(n, **kw):
+    def timed(self, n, **kw):
+        torch = self.torch
         for _ in range(2):
-            iteration(**kw)
+            self.iteration(**kw)
         torch.cuda.synchronize()
         t = time.perf_counter()
         for _ in range(n):
-            iteration(**kw)
+            self.iteration(**kw)
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / n
 
-    # one-pass variants: reduce+AdamW without writing the gradient (4 R_c + 24 B/element), and
-    # accumulate+snapshot at every microbatch (s_g + 12 resp. s_g + 8 instead of s_g + 8 + 8 resp. s_g + 4 + 8)
-    dtf = timed(ns, fused=True)
-    b_fused = bpe["accumulate"] + 4 * W + 24
-    fused = dict(ms_per_step=dtf * 1e3, bytes_per_elem=b_fused, GBps=b_fused * N / dtf / 1e9,
-                 microbatches_per_s=M / dtf)
-    dte = timed(ns, fused=True, snapshot_every=True)
-    b_every = W * (s_g + 8) + (M - W) * (s_g + 12) + 4 * W + 24
-    every = dict(ms_per_step=dte * 1e3, bytes_per_elem=b_every, GBps=b_every * N / dte / 1e9,
-                 microbatches_per_s=M / dte)
+    def measure(self, steps, warmup, settle_seconds):
+        """Settle, warm up, time exactly `steps` iterations bracketed by synchronisation; per-phase events inside
+        the timed region give every kernel's rate and the per-iteration distribution."""
+        torch = self.torch
+        W, G, N, M, s_g, bpe = self.W, self.G, self.N, self.M, self.s_g, self.bpe
+        settle_s, settle_windows = self.settle(settle_seconds) if settle_seconds > 0 else (0.0, 0)
+        for _ in range(warmup):
+            self.iteration()
+        torch.cuda.synchronize()
+        marks = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.iteration(marks)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        per_iter = [m[0].elapsed_time(m[4]) for m in marks]                                  # ms, events
+        phase = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]     # ms per iteration
+        n_rmw = (G - 1) * W
+        rmw_ms = phase[1] / n_rmw
+        k_gbs = dict(accumulate_first=W * (s_g + 4) * N / phase[0] / 1e6, accumulate_rmw=(s_g + 8) * N / rmw_ms / 1e6,
+                     reduce=bpe["reduce"] * N / phase[2] / 1e6, adamw=28 * N / phase[3] / 1e6)
+        gbs = bpe["total"] * N / (dt / steps) / 1e9
+        gname = "bf16" if self.c["bf16"] else "float"
+        return dict(
+            value=gbs, ms_per_step=dt * 1e3 / steps, steps=steps, warmup=warmup,
+            pct_of_hbm_peak=100.0 * gbs / HBM_PEAK_GBS, microbatches_per_s=M / (dt / steps),
+            iteration_ms_events=quantiles(per_iter),
+            settle={"seconds": settle_s, "windows": settle_windows, "untimed": True},
+            kernel_GBps=k_gbs,
+            phase_ms=dict(accumulate_first=phase[0], accumulate_rmw=phase[1], reduce=phase[2], adamw=phase[3]),
+            roofline={"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % gname, "achieved": k_gbs["accumulate_rmw"],
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
+                      "traffic": read_traffic(self.k), "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,
+                      "launches_timed": n_rmw * len(marks)},
+            config={"workload": WORKLOAD_TEXT[self.k], "grad_dtype": "bf16" if self.c["bf16"] else "f32",
+                    "replicas": W, "microbatches": M, "n_elems": N, "n_tensors": self.T,
+                    "bytes_per_elem": bpe["total"], "grad_pool_buffers": POOL})
 
-    # launch-bound shards: one accumulate_many launch per microbatch slot + the fused step (G + 1 launches)
-    def iteration_batched():
+    # ------------------------------------------------------------------------------------------ extras
+    def extras(self, base_ms, steps):
+        torch, B, ctx, W, G, T, N, M, s_g, bpe = self.torch, self.B, self.ctx, self.W, self.G, self.T, self.N, self.M, self.s_g, self.bpe
+        stream, gptr, gcode, pool, c = self.stream, self.gptr, self.gcode, self.pool, self.c
+        out = {}
+        ns = max(3, steps // 5)
+        # the same iteration with a snapshot of every replica before the reduction (Alg. 1, snapshot step)
+        dts = self.timed(ns, snapshot=True)
+        out["with_snapshot"] = dict(ms_per_step=dts * 1e3, bytes_per_elem=bpe["total"] + 8 * W,
+                                    GBps=(bpe["total"] + 8 * W) * N / dts / 1e9)
+        # one-pass variants: reduce+AdamW without writing the gradient (4 R_c + 24 B/element), and
+        # accumulate+snapshot at every microbatch (s_g + 12 resp. s_g + 8 instead of s_g + 8 + 8 resp. s_g + 4 + 8)
+        dtf = self.timed(ns, fused=True)
+        b_fused = bpe["accumulate"] + 4 * W + 24
+        out["fused_reduce_adamw"] = dict(ms_per_step=dtf * 1e3, bytes_per_elem=b_fused, GBps=b_fused * N / dtf / 1e9,
+                                         microbatches_per_s=M / dtf)
+        marks = []
+        for _ in range(ns):
+            e0, e1 = self.ev(), self.ev()
+            for r in range(W):
+                for k in range(G):
+                    assert B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream) == 0
+            e0.record()
+            assert B.recover_reduce_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
+                                               0, stream) == 0
+            e1.record()
+            marks.append((e0, e1))
+            assert B.recover_policy_adjust(ctx, [], W)[0] == 0
+        torch.cuda.synchronize()
+        fk = sorted(a.elapsed_time(b) for a, b in marks)[len(marks) // 2]
+        out["fused_reduce_adamw"]["kernel_ms"] = fk
+        out["fused_reduce_adamw"]["kernel_GBps"] = (4 * W + 24) * N / fk / 1e6
+        dte = self.timed(ns, fused=True, snapshot_every=True)
+        b_every = W * (s_g + 8) + (M - W) * (s_g + 12) + 4 * W + 24
+        out["fused_snapshot_every_microbatch"] = dict(ms_per_step=dte * 1e3, bytes_per_elem=b_every,
+                                                      GBps=b_every * N / dte / 1e9, microbatches_per_s=M / dte)
+
+        # snapshot and restore alone (one launch each for all replicas), and the chip's ceilings with the
+        # library's own kernels on the same buffers: copy = the snapshot; read-only = recover_compare, which
+        # streams two buffers and writes nothing.
         for k in range(G):
-            rc, _ = B.recover_accumulate_many(ctx, list(range(W)), [r + W * k for r in range(W)],
-                                              [gptr[(k * W + r) % POOL] for r in range(W)], gcode, stream)
-            assert rc == 0, rc
-        assert B.recover_reduce_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
-                                           0, stream) == 0
-        rc, _ = B.recover_policy_adjust(ctx, [], W)
-        assert rc == 0
+            for r in range(W):
+                assert B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream) == 0
+        snap_t, rest_t, cmp_t = [], [], []
+        res = torch.empty(5, dtype=torch.int64, device="cuda:0")
+        for i in range(6):
+            e = [self.ev() for _ in range(4)]
+            e[0].record()
+            assert B.recover_snapshot(ctx, -1, 0, T, stream) == 0
+            e[1].record()
+            assert B.recover_restore(ctx, -1, 0, stream) == 0
+            e[2].record()
+            assert B.recover_compare(self.sh.acc[i % W].data_ptr(), self.sh.snap[(i + 1) % W].data_ptr(), N, res.data_ptr(),
+                                     stream) == 0
+            e[3].record()
+            torch.cuda.synchronize()
+            if i:
+                snap_t.append(e[0].elapsed_time(e[1]))
+                rest_t.append(e[1].elapsed_time(e[2]))
+                cmp_t.append(e[2].elapsed_time(e[3]))
+        med = lambda v: sorted(v)[len(v) // 2]
+        out["snapshot_all_replicas"] = dict(ms=med(snap_t), GBps=8 * W * N / med(snap_t) / 1e6, launches=1)
+        out["restore_all_replicas"] = dict(ms=med(rest_t), GBps=8 * W * N / med(rest_t) / 1e6, launches=1)
+        out["ceilings"] = dict(copy_GBps=8 * W * N / min(snap_t) / 1e6, read_only_GBps=8 * N / min(cmp_t) / 1e6,
+                               what="best of 5: copy = recover_snapshot of all replicas (k_copy_many); read-only = "
+                                    "recover_compare over two buffers (k_compare)")
 
-    batched = None
-    if a.workload == 1:
+        # Non-blocking restoration (Alg. 5): rewind every replica from its snapshot while the main stream
+        # generates the next microbatch's gradient (the stand-in for the extended pass's forward/backward),
+        # then re-reduce.  Serial = all on one stream; overlapped = the rewind on a side stream, ordered by
+        # the context's events.
+        S, synth = self.S, self.synth
+
+        def restore_then_reduce(side):
+            e0, e1 = self.ev(), self.ev()
+            e0.record()
+            assert B.recover_restore(ctx, -1, 0, stream if side is None else side.cuda_stream) == 0
+            synth.fill_device(pool[0], c["seed"], S.TAG_GRAD, 99, 0, c["scale"], c["kind"])
+            assert B.recover_reduce(ctx, 0, T, 0, stream) == 0
+            e1.record()
+            return e0, e1
+
+        side = torch.cuda.Stream()
+        pairs = {"serial": [], "overlapped": []}
+        for i in range(8):
+            for name, sd in (("serial", None), ("overlapped", side)):
+                pairs[name].append(restore_then_reduce(sd))
+        torch.cuda.synchronize()
+        ro = {k: sum(a_.elapsed_time(b_) for a_, b_ in v[2:]) / len(v[2:]) for k, v in pairs.items()}
+        out["nonblocking_restore"] = dict(serial_ms=ro["serial"], overlapped_ms=ro["overlapped"],
+                                          what="restore of %d replicas + generation of one gradient + reduce" % W)
+        assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], stream) == 0
+        assert B.recover_policy_adjust(ctx, [], W)[0] == 0
+
+        # One failure iteration of this workload, timed as a whole (Alg. 1 with Alg. 4-6): replicas crash
+        # after two microbatches, half of the tensors are snapshotted and all-reduced in place before the
+        # failure shows, then rewind, extended pass, snapshot, reduce, AdamW, advancement.
+        if W >= 4 and G >= 2:
+            from paper_2605_11215_amd.loop import run_iteration, view_shard
+            lost = {W // 2 - 1: min(2, G), W - 2: min(2, G)} if W >= 8 else {W // 2 - 1: min(2, G)}
+            torch.cuda.synchronize()
+            t4 = time.perf_counter()
+            res_ = run_iteration(self.sh, view_shard, 0, lambda t, mb: pool[mb % POOL], W, dying=lost,
+                                 fidelity_k=T // 2 or 1, hp=HP)
+            torch.cuda.synchronize()
+            dtf2 = time.perf_counter() - t4
+            n_acc = sum(len(v) for v in res_["ids"].values()) + sum(lost.values())
+            out["failure_iteration"] = dict(ms=dtf2 * 1e3, lost_replicas=sorted(lost), accumulates=n_acc,
+                                            committed_microbatches=sum(len(v) for v in res_["ids"].values()),
+                                            extra_slots=res_["decisions"][0]["G_ext"],
+                                            vs_failure_free=dtf2 * 1e3 / base_ms)
+        return out
+
+    def batched(self, steps):
+        """Launch-bound shards: one accumulate_many launch per microbatch slot + the fused step (G + 1 launches),
+        and the same iteration captured once into a HIP graph (step count on the device) and replayed."""
+        torch, B, W, G, N, M, gptr, gcode, stream, c = self.torch, self.B, self.W, self.G, self.N, self.M, self.gptr, self.gcode, self.stream, self.c
+        b_fused = self.bpe["accumulate"] + 4 * W + 24
+        hp = (HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"])
+
+        def one(ctx, s):
+            for k in range(G):
+                rc, _ = B.recover_accumulate_many(ctx, list(range(W)), [r + W * k for r in range(W)],
+                                                  [gptr[(k * W + r) % POOL] for r in range(W)], gcode, s)
+                assert rc == 0, rc
+            assert B.recover_reduce_adamw_step(ctx, *hp, 0, s) == 0
+            assert B.recover_policy_adjust(ctx, [], W)[0] == 0
+
         for _ in range(3):
-            iteration_batched()
+            one(self.ctx, stream)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
-        for _ in range(a.steps):
-            iteration_batched()
+        for _ in range(steps):
+            one(self.ctx, stream)
         torch.cuda.synchronize()
-        dtb = (time.perf_counter() - t2) / a.steps
-        batched = dict(ms_per_step=dtb * 1e3, launches=G + 1, bytes_per_elem=b_fused, GBps=b_fused * N / dtb / 1e9,
-                       microbatches_per_s=M / dtb)
-        # the same iteration captured once into a HIP graph (step count on the device) and replayed
-        sg = B.Shard(W, G, off, device="cuda:0", snapshots=False, device_step=True)
-        synth.fill_device(sg.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=N)
+        dtb = (time.perf_counter() - t2) / steps
+        out = dict(ms_per_step=dtb * 1e3, launches=G + 1, bytes_per_elem=b_fused, GBps=b_fused * N / dtb / 1e9,
+                   microbatches_per_s=M / dtb)
+        sg = B.Shard(W, G, self.off, device="cuda:0", snapshots=False, device_step=True)
+        self.synth.fill_device(sg.param, c["seed"], self.S.TAG_PARAM, 0, 0, 0.02, n=N)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            cs = torch.cuda.current_stream().cuda_stream
-            for k in range(G):
-                rc, _ = B.recover_accumulate_many(sg.ctx, list(range(W)), [r + W * k for r in range(W)],
-                                                  [gptr[(k * W + r) % POOL] for r in range(W)], gcode, cs)
-                assert rc == 0, rc
-            assert B.recover_reduce_adamw_step(sg.ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"],
-                                               HP["weight_decay"], 0, cs) == 0
-            assert B.recover_policy_adjust(sg.ctx, [], W)[0] == 0
+            one(sg.ctx, torch.cuda.current_stream().cuda_stream)
         for _ in range(3):
             graph.replay()
         torch.cuda.synchronize()
         t3 = time.perf_counter()
-        for _ in range(a.steps):
+        for _ in range(steps):
             graph.replay()
         torch.cuda.synchronize()
-        dtg = (time.perf_counter() - t3) / a.steps
-        batched["graph_replay"] = dict(ms_per_step=dtg * 1e3, GBps=b_fused * N / dtg / 1e9, microbatches_per_s=M / dtg)
+        dtg = (time.perf_counter() - t3) / steps
+        out["graph_replay"] = dict(ms_per_step=dtg * 1e3, GBps=b_fused * N / dtg / 1e9, microbatches_per_s=M / dtg)
+        sg.close()
+        return out
 
-    # Non-blocking restoration (Alg. 5): rewind every replica from its snapshot while the main stream
-    # generates the next microbatch's gradient (the stand-in for the extended pass's forward/backward),
-    # then re-reduce.  Serial = all on one stream; overlapped = the rewind on a side stream, ordered by
-    # the context's events.
-    def restore_then_reduce(side):
-        e0, e1 = ev(), ev()
-        e0.record()
-        if side is None:
-            assert B.recover_restore(ctx, -1, 0, stream) == 0
-        else:
-            assert B.recover_restore(ctx, -1, 0, side.cuda_stream) == 0
-        synth.fill_device(pool[0], c["seed"], S.TAG_GRAD, 99, 0, c["scale"], c["kind"])
-        assert B.recover_reduce(ctx, 0, T, 0, stream) == 0
-        e1.record()
-        return e0, e1
 
-    for k in range(G):
-        for r in range(W):
-            assert B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream) == 0
-    assert B.recover_snapshot(ctx, -1, 0, T, stream) == 0
-    side = torch.cuda.Stream()
-    pairs = {"serial": [], "overlapped": []}
-    for i in range(12):
-        for name, sd in (("serial", None), ("overlapped", side)):
-            pairs[name].append(restore_then_reduce(sd))
-    torch.cuda.synchronize()
-    restore_overlap = {k: sum(a_.elapsed_time(b_) for a_, b_ in v[2:]) / len(v[2:]) for k, v in pairs.items()}
-    restore_overlap = dict(serial_ms=restore_overlap["serial"], overlapped_ms=restore_overlap["overlapped"],
-                           what="restore of %d replicas + generation of one gradient + reduce" % W)
-    assert B.recover_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], stream) == 0
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-slice", type=int, default=1 << 24)
+    ap.add_argument("--cpu-iters", type=int, default=40)
+    ap.add_argument("--settle-seconds", type=float, default=15.0,
+                    help="upper bound of the untimed settling phase before the warmup (see Leg.settle)")
+    ap.add_argument("--workload", type=int, default=5, choices=[1, 2, 3, 4, 5],
+                    help="the headline workload (default 5 = configs[4], the largest single-GPU configuration)")
+    ap.add_argument("--per-config", default="2,3,4",
+                    help="comma list of further workloads timed after the headline ('' = none)")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed region (for profiling runs)")
+    ap.add_argument("--separate-allocations", action="store_true",
+                    help="one device allocation per buffer instead of one slab per context (placement A/B)")
+    ap.add_argument("--slab-pad-kib", type=int, default=4096, help="padding between the buffers of a slab")
+    ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's HBM); "
+              "--gpus %d is not supported" % a.gpus, file=sys.stderr)
+        sys.exit(2)
 
-    # One failure iteration of this workload's schedule, timed as a whole (Alg. 1 with Alg. 4-6): two
-    # replicas crash after two microbatches, half of the tensors are snapshotted and all-reduced in
-    # place before the failure shows, then rewind, extended pass, snapshot, reduce, AdamW, advancement.
-    failure_iteration = None
-    if W >= 4 and G >= 2:
-        from paper_2605_11215_amd.loop import run_iteration, view_shard
-        lost = {W // 2 - 1: min(2, G), W - 2: min(2, G)}
-        torch.cuda.synchronize()
-        t4 = time.perf_counter()
-        res = run_iteration(sh, view_shard, 0, lambda t, mb: pool[mb % POOL], W, dying=lost, fidelity_k=T // 2 or 1,
-                            hp=HP)
-        torch.cuda.synchronize()
-        dtf2 = time.perf_counter() - t4
-        n_acc = sum(len(v) for v in res["ids"].values()) + sum(lost.values())
-        failure_iteration = dict(ms=dtf2 * 1e3, lost_replicas=sorted(lost), accumulates=n_acc,
-                                 committed_microbatches=sum(len(v) for v in res["ids"].values()),
-                                 extra_slots=res["decisions"][0]["G_ext"], vs_failure_free=dtf2 / (dt / a.steps))
+    import torch
+    from paper_2605_11215_amd import binding as B
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; this library has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    B.lib()
+    SLAB["on"], SLAB["pad"] = not a.separate_allocations, a.slab_pad_kib << 10
+    for kv in filter(None, a.tuning.split(",")):
+        k, v = kv.split("=")
+        assert B.recover_set_tuning(int(k), int(v)) == 0, kv
+    torch.cuda.set_device(0)
 
+    leg = Leg(a.workload)
+    head = leg.measure(a.steps, a.warmup, a.settle_seconds)
     out = {
         "metric": "effective HBM GB/s (and % of 8 TB/s) for accumulate+reduce+AdamW per iteration",
-        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[a.workload], "grad_dtype": "bf16" if c["bf16"] else "f32",
-                   "replicas": W, "microbatches": M, "n_elems": N, "n_tensors": T,
-                   "bytes_per_elem": bpe["total"], "grad_pool_buffers": POOL},
-        "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": ARITHMETIC, "data": "synthetic", "config": head["config"],
+        "pct_of_hbm_peak": head["pct_of_hbm_peak"],
         "paper_context": "context only, other hardware: the paper reports 2.23x effective throughput over "
                          "checkpoint-restart after successive failures (128 x A100-40GB, 7B LLaMA-style model) and "
                          "evaluates up to 512 GPUs; it gives no bandwidth or per-kernel figure for this path",
-        "settle": {"seconds": settle_s, "windows": settle_windows, "untimed": True},
-        "microbatches_per_s": M / (dt / a.steps),
-        "kernel_GBps": k_gbs,
-        "phase_ms": dict(accumulate_first=phase[0], accumulate_rmw=phase[1], reduce=phase[2], adamw=phase[3]),
-        "with_snapshot": with_snapshot,
-        "fused_reduce_adamw": fused,
-        "fused_snapshot_every_microbatch": every,
-        "batched_launches": batched,
-        "nonblocking_restore": restore_overlap,
-        "failure_iteration": failure_iteration,
-        "roofline": {"bound": "hbm", "kernel": "k_accumulate<%s, RMW>" % ("bf16" if c["bf16"] else "float"), "achieved": k_gbs["accumulate_rmw"],
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs["accumulate_rmw"] / HBM_PEAK_GBS,
-                     "traffic": read_traffic() if a.workload == 2 else None, "bytes_per_launch": (s_g + 8) * N, "avg_launch_ms": rmw_ms,
-                     "launches_timed": n_rmw * len(marks)},
     }
+    for k in ("settle", "microbatches_per_s", "iteration_ms_events", "kernel_GBps", "phase_ms"):
+        out[k] = head[k]
+    if not a.no_extras:
+        out.update(leg.extras(head["ms_per_step"], a.steps))
+        out["batched_launches"] = leg.batched(a.steps) if a.workload == 1 else None
+    out["roofline"] = head["roofline"]
+    cpu_slices = None
     if not a.no_cpu_baseline:
-        n = min(a.cpu_slice, N)
-        slices = [g[:n].float().cpu().numpy() for g in pool]
-        out["cpu_baseline"] = cpu_baseline(c, slices, a.cpu_iters)
-    sh.close()
+        n = min(a.cpu_slice, leg.N)
+        cpu_slices = (leg.c, [g[:n].float().cpu().numpy() for g in leg.pool])
+    leg.close()
+
+    per = {}
+    for k in [int(x) for x in a.per_config.split(",") if x]:
+        if k == a.workload:
+            continue
+        lk = Leg(k)
+        est_ms = lk.bpe["total"] * lk.N / 6.5e9
+        r = lk.measure(max(5, min(40, int(1500.0 / est_ms))), 2, a.settle_seconds)
+        if not a.no_extras:
+            dtf = lk.timed(max(3, r["steps"] // 4), fused=True)
+            b_fused = lk.bpe["accumulate"] + 4 * lk.W + 24
+            r["fused_reduce_adamw"] = dict(ms_per_step=dtf * 1e3, bytes_per_elem=b_fused, GBps=b_fused * lk.N / dtf / 1e9)
+        per["configs[%d]" % (k - 1)] = r
+        lk.close()
+    out["per_config"] = per
+    if cpu_slices is not None:
+        out["cpu_baseline"] = cpu_baseline(cpu_slices[0], cpu_slices[1], a.cpu_iters)
     print(json.dumps(out))
 
 

@@ -220,7 +220,7 @@ int recover_query(recover_ctx *ctx, recover_decision *out);
  * Writes min(count, cap) ids and returns the count, or a negative code. */
 int recover_committed_ids(recover_ctx *ctx, int replica, uint32_t *ids_out, int cap);
 
-/* Verification support (not a step of the path): compares two device fp32 buffers of n elements on the GPU.
+/* Verification support (not a step of the path): compares two device fp32 buffers (16-byte aligned) of n elements on the GPU.
  * The 40-byte result is written to DEVICE memory `out_device` (caller-owned, 8-byte aligned), asynchronously on
  * the stream; the caller copies it back.  max_abs_diff and max_abs_ref skip NaNs; the checksums are
  * sum(bits[i] * (2 i + 1)) mod 2^64, so equal checksums of x and ref with n_mismatch == 0 mean equal buffers.
@@ -254,11 +254,11 @@ enum { /* kernel classes that have a launch shape of their own */
 };
 enum { /* keys of recover_set_tuning / recover_get_tuning */
   RECOVER_TUNE_NONTEMPORAL = 1, /* {0, 1}: streaming cache hints on loads and stores */
-  RECOVER_TUNE_GRID_CAP = 2,    /* 0 = one tile per workgroup, else grid-stride over at most this many workgroups */
-  RECOVER_TUNE_XCD_CHUNKED = 6, /* {0, 1}: accumulate gives each XCD one contiguous eighth of the range */
   RECOVER_TUNE_THREADS = 7,     /* {64, 256}: lanes per workgroup */
   RECOVER_TUNE_VECS = 16,       /* + kernel class: 128-bit vectors per lane per stream {1, 2, 4} */
-  RECOVER_TUNE_WAVES = 32       /* + kernel class: wavefronts resident per CU, 0 = hardware limit, else 2..32 */
+  RECOVER_TUNE_WAVES = 32,      /* + kernel class: wavefronts resident per CU, 0 = hardware limit, else 2..32 */
+  RECOVER_TUNE_DEPTH = 48       /* + RECOVER_KERNEL_REDUCE or _REDUCE_ADAMW: contributors a wavefront loads at a time {1, 2};
+                                   _REDUCE_ADAMW also {3, 4} = {1, 2} with the optimiser state loaded before the walk */
 };
 int recover_set_tuning(int key, int value);
 int recover_get_tuning(int key, int *value);

@@ -24,7 +24,7 @@ MAX_REPLICAS = 64
 FUSED_WRITE_GRAD = 1
 (KERNEL_ACCUMULATE_FIRST_F32, KERNEL_ACCUMULATE_RMW_F32, KERNEL_ACCUMULATE_FIRST_BF16, KERNEL_ACCUMULATE_RMW_BF16,
  KERNEL_COPY, KERNEL_REDUCE, KERNEL_ADAMW, KERNEL_REDUCE_ADAMW, KERNEL_CLASSES) = range(9)
-TUNE_NONTEMPORAL, TUNE_GRID_CAP, TUNE_XCD_CHUNKED, TUNE_THREADS, TUNE_VECS, TUNE_WAVES = 1, 2, 6, 7, 16, 32
+TUNE_NONTEMPORAL, TUNE_THREADS, TUNE_VECS, TUNE_WAVES, TUNE_DEPTH = 1, 7, 16, 32, 48
 
 EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_accumulate_many",
            "recover_accumulate_snapshot",
@@ -246,6 +246,25 @@ def recover_get_tuning(key):
     return code, v.value
 
 
+def alloc_slab(specs, device="cuda:0", pad_bytes=4 << 20, align=2 << 20):
+    """One device allocation carved into zero-filled flat tensors: specs = [(torch dtype, numel), ...].  Every
+    tensor starts `align`-aligned inside the slab and is followed by `pad_bytes` of padding.  A single
+    allocation gives the buffers of a context fixed relative placement (separate allocations land wherever
+    the driver puts them, and HBM efficiency of the multi-stream kernels then differs from run to run)."""
+    import torch
+    sizes = [n * torch.empty(0, dtype=dt).element_size() for dt, n in specs]
+    offs, total = [], 0
+    for b in sizes:
+        offs.append(total)
+        total += (b + align - 1) // align * align + pad_bytes
+    slab = torch.zeros(total + align, dtype=torch.uint8, device=device)
+    base = (-slab.data_ptr()) % align
+    out = []
+    for (dt, n), o, b in zip(specs, offs, sizes):
+        out.append(slab[base + o: base + o + b].view(dt))
+    return slab, out
+
+
 class Shard:
     """Buffers of one context allocated with PyTorch on `device`, plus the calls on it.
 
@@ -254,7 +273,9 @@ class Shard:
     current stream."""
 
     def __init__(self, W_init, G_init, tensor_offsets, device="cuda:0", snapshots=True, flags=0, param_bf16=False,
-                 host_only=False, device_step=False):
+                 host_only=False, device_step=False, slab=False, slab_pad=4 << 20, extra=()):
+        """slab: all buffers (and the `extra` = [(dtype, numel), ...] tensors, returned in self.extra) are carved
+        from one allocation, see alloc_slab."""
         import torch
         self.torch = torch
         self.W, self.G = W_init, G_init
@@ -267,11 +288,19 @@ class Shard:
             code, self.ctx = recover_init(W_init, G_init, self.off, None, [0] * W_init if snapshots else None,
                                           0, 0, 0, 0, 0, flags)
         else:
-            z = lambda dt=torch.float32: torch.zeros(max(self.N, 4), dtype=dt, device=device)
+            n = max(self.N, 4)
+            if slab:
+                n_f32 = W_init * (2 if snapshots else 1) + 4
+                specs = [(torch.float32, n)] * n_f32 + ([(torch.bfloat16, n)] if param_bf16 else []) + list(extra)
+                self._slab, bufs = alloc_slab(specs, device, slab_pad)
+                z = lambda dt=torch.float32: bufs.pop(0)
+            else:
+                z = lambda dt=torch.float32: torch.zeros(n, dtype=dt, device=device)
             self.acc = [z() for _ in range(W_init)]
             self.snap = [z() for _ in range(W_init)] if snapshots else None
             self.grad_out, self.param, self.exp_avg, self.exp_avg_sq = z(), z(), z(), z()
             self.param_bf16 = z(torch.bfloat16) if param_bf16 else None
+            self.extra = [z() for _ in extra] if slab else [torch.zeros(k, dtype=dt, device=device) for dt, k in extra]
             self.step_state = torch.zeros(8, dtype=torch.int64, device=device) if device_step else None
             code, self.ctx = recover_init(
                 W_init, G_init, self.off, [t.data_ptr() for t in self.acc],

@@ -27,17 +27,15 @@ enum KernelClass {
 // much more than ~48 KiB of loads per CU are in flight (the open DRAM pages thrash), so the kernels
 // with several streams per wavefront run faster with fewer resident wavefronts.  The limit is imposed by
 // giving every workgroup a share of the CU's 160 KiB of LDS that it never touches.
+// depth (reduce kernels only): contributors whose loads a wavefront has in flight at a time {1, 2}.
 struct Shape {
-  int vecs, waves;
+  int vecs, waves, depth;
 };
 
 struct Tuning {
   int threads = 64;     // lanes per workgroup: 64 (one wavefront) or 256
   int nontemporal = 1;  // streaming cache hints on loads and stores
-  int grid_cap = 0;     // 0: one tile per workgroup; else grid-stride over at most this many
-  int xcd_chunked = 0;  // accumulate: 1 = workgroup b works in the b%8-th eighth of the range (one
-                        // contiguous region per XCD) instead of tile b
-  Shape shape[kNumClasses] = {{1, 0}, {1, 24}, {1, 0}, {1, 0}, {1, 0}, {1, 0}, {1, 10}, {1, 8}};
+  Shape shape[kNumClasses] = {{1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 14, 2}, {1, 10, 0}, {1, 12, 2}};
 };
 Tuning &tuning();
 
@@ -69,14 +67,15 @@ hipError_t launch_accumulate_many(const AccumulateManyArgs &a, int n_pairs, bool
 // snap != nullptr: the new accumulator value is stored to snap as well (accumulate + snapshot in one pass)
 hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool grad_is_bf16, bool first, size_t begin,
                              size_t end, hipStream_t s);
-hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s);
+// restore only selects the kernel's name (snapshot or rewind) for traces
+hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, bool restore, hipStream_t s);
 
 // dst[i][begin, end) = src[i][begin, end) for n_pairs buffer pairs in one launch.
 struct CopyManyArgs {
   float *dst[kMaxReplicas];
   const float *src[kMaxReplicas];
 };
-hipError_t launch_copy_many(const CopyManyArgs &a, int n_pairs, size_t begin, size_t end, hipStream_t s);
+hipError_t launch_copy_many(const CopyManyArgs &a, int n_pairs, size_t begin, size_t end, bool restore, hipStream_t s);
 hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStream_t s);
 // Per-step constants of AdamW: decay_mul = 1 - lr wd, step_size = lr / (1 - beta1^t),
 // inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).
@@ -115,6 +114,9 @@ struct StepState {
   uint64_t reserved;
 };
 static_assert(sizeof(StepState) == 64, "StepState is 64 bytes");
+
+// Zero-fills *st with a one-thread kernel (no memset node, so the call can be captured into a graph).
+hipError_t launch_clear_step_state(StepState *st, hipStream_t s);
 
 // Advances *st by one step and stores that step's constants in st->args (one thread).
 hipError_t launch_adam_prologue(StepState *st, float lr, float beta1, float beta2, float eps, float weight_decay,

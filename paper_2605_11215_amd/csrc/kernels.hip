@@ -1,17 +1,19 @@
 // gfx950 kernels of the gradient path.  Every step is an elementwise stream over flat fp32
 // buffers, bound by HBM bandwidth, so the design is the same everywhere: one 128-bit load or
 // store per lane per access (a wavefront moves 1 KiB of consecutive bytes per instruction),
-// one-wavefront workgroups with one tile each (a finished wavefront frees its slot at once; measured
+// one-wavefront workgroups with ONE tile each (a finished wavefront frees its slot at once; measured
 // 4 % faster than four-wavefront groups), U independent vectors in flight per lane before the first
 // use, 64-bit element indices (a shard can exceed 2^32 bytes), no LDS (no element is used twice) and
-// no atomics (the sums have a fixed order).  Ranges that do not start or end on a 16-byte boundary
-// get their ragged ends from a few lanes of workgroup 0.
+// no atomics (the sums have a fixed order).
 //
-// Every kernel body exists twice, selected by a wavefront-uniform test: FULL tiles (all but at most
-// the last one) run without any per-lane bounds test, so all their loads are issued back to back
-// before the first wait; the last, partial tile masks each access.  Raw bf16 words are widened only
-// after every load of the tile has been issued (widening right after the load would put a wait
-// between the gradient load and the accumulator load).
+// A wavefront moves only a few KiB in its whole life, so its prologue counts: the kernels take
+// pointers that the host has already advanced to the first aligned vector, and a vector count;
+// there is no tile loop, no range arithmetic and no ragged-end code in them.  Ranges that do not
+// start or end on a 16-byte boundary get their (at most six) ragged elements from a second,
+// eight-lane launch of a scalar kernel.  Every kernel body exists twice, selected by a
+// wavefront-uniform test: full tiles (all but the last) run without per-lane bounds tests, so all
+// their loads are issued back to back before the first wait; the last, partial tile masks each
+// access.  Raw bf16 words are widened only after every load of the tile has been issued.
 #include "kernels.h"
 
 #include <type_traits>
@@ -42,6 +44,7 @@ static Span make_span(size_t begin, size_t end) {
   s.nvec = (end - vb) / 4;
   return s;
 }
+static bool ragged(const Span &sp) { return sp.vbegin != sp.begin || sp.vbegin + sp.nvec * 4 != sp.end; }
 
 // Element index of the k-th ragged element (head first, then tail), or end if k is past them.
 __device__ inline size_t ragged_index(const Span &sp, unsigned k) {
@@ -67,7 +70,15 @@ __device__ inline void st(T *p, T v) {
 using True = std::true_type;
 using False = std::false_type;
 
-// Runs body(True) on a full tile and body(False) on the partial one; `full` is wavefront-uniform.
+// The calling workgroup's tile: index of its lane's first vector, and whether the whole tile lies inside
+// [0, nvec) (wavefront-uniform).  T * U vectors per tile, lane l takes vectors base + T * u.
+template <int T, int U>
+__device__ inline size_t tile_base(size_t nvec, bool *full) {
+  const size_t t0 = size_t(blockIdx.x) * (T * U);
+  *full = t0 + T * U <= nvec;
+  return t0 + threadIdx.x;
+}
+// Runs body(True) on a full tile and body(False) on the partial one.
 template <typename F>
 __device__ inline void on_tile(bool full, F &&body) {
   if (full)
@@ -104,75 +115,71 @@ __device__ inline float load_grad1(const uint16_t *g, size_t i) { return bf16_to
 
 // ---------------------------------------------------------------------------------------------
 // accumulate: acc[i] = acc[i] + widen(g[i]);  FIRST: acc[i] = (+0) + widen(g[i])
+// a4, s4, g4 point at the first aligned vector of the range.
 // ---------------------------------------------------------------------------------------------
 template <typename G, int T, int U, bool NT, bool FIRST, bool SNAP>
-__device__ inline void accumulate_tiles(float *__restrict__ acc, float *__restrict__ snap, const G *__restrict__ g,
-                                        const Span &sp, size_t first, size_t stride, size_t ntiles) {
+__device__ inline void accumulate_tile(f32x4 *__restrict__ a4, f32x4 *__restrict__ s4,
+                                       const typename Grad4<G>::raw *__restrict__ g4, size_t nvec) {
   typedef typename Grad4<G>::raw Raw;
-  f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
-  f32x4 *s4 = SNAP ? reinterpret_cast<f32x4 *>(snap + sp.vbegin) : nullptr;
-  const Raw *g4 = reinterpret_cast<const Raw *>(g + sp.vbegin);
-  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-  for (size_t tile = first; tile < ntiles; tile += stride) {
-    const size_t base = tile * size_t(T * U) + threadIdx.x;
-    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
-      constexpr bool FULL = decltype(full)::value;
-      Raw x[U];
-      f32x4 a[U];
-      bool ok[U];
+  bool full;
+  const size_t base = tile_base<T, U>(nvec, &full);
+  on_tile(full, [&](auto is_full) {
+    constexpr bool FULL = decltype(is_full)::value;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    Raw x[U];
+    f32x4 a[U];
+    bool ok[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
+    for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) x[u] = ld<NT>(g4 + base + size_t(T) * u);
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) x[u] = ld<NT>(g4 + base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) a[u] = FIRST ? zero : ld<NT>(a4 + base + size_t(T) * u);
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) a[u] = FIRST ? zero : ld<NT>(a4 + base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (ok[u]) {
-          const f32x4 r = a[u] + Grad4<G>::widen(x[u]);
-          st<NT>(a4 + base + size_t(T) * u, r);
-          if (SNAP) st<NT>(s4 + base + size_t(T) * u, r);
-        }
+    for (int u = 0; u < U; ++u) {
+      if (ok[u]) {
+        const f32x4 r = a[u] + Grad4<G>::widen(x[u]);
+        st<NT>(a4 + base + size_t(T) * u, r);
+        if (SNAP) st<NT>(s4 + base + size_t(T) * u, r);
       }
-    });
-  }
+    }
+  });
 }
 
 template <typename G, int T, int U, bool NT, bool FIRST, bool SNAP>
-__global__ __launch_bounds__(T) void k_accumulate(float *__restrict__ acc, float *__restrict__ snap,
-                                                  const G *__restrict__ g, Span sp, size_t ntiles, int xcd_chunked) {
-  size_t first = blockIdx.x, stride = gridDim.x;
-  if (xcd_chunked) {  // grid = 8 * ceil(ntiles / 8): one tile per workgroup, XCD x owns the x-th eighth
-    first = size_t(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    stride = ntiles;
-  }
-  accumulate_tiles<G, T, U, NT, FIRST, SNAP>(acc, snap, g, sp, first, stride, ntiles);
-  if (blockIdx.x == 0 && threadIdx.x < 8) {
-    const size_t i = ragged_index(sp, threadIdx.x);
-    if (i < sp.end) {
-      const float r = (FIRST ? 0.f : acc[i]) + load_grad1(g, i);
-      acc[i] = r;
-      if (SNAP) snap[i] = r;
-    }
+__global__ __launch_bounds__(T) void k_accumulate(f32x4 *__restrict__ a4, f32x4 *__restrict__ s4,
+                                                  const typename Grad4<G>::raw *__restrict__ g4, size_t nvec) {
+  accumulate_tile<G, T, U, NT, FIRST, SNAP>(a4, s4, g4, nvec);
+}
+
+template <typename G, bool FIRST, bool SNAP>
+__global__ __launch_bounds__(64) void k_accumulate_ragged(float *__restrict__ acc, float *__restrict__ snap,
+                                                          const G *__restrict__ g, Span sp) {
+  const size_t i = ragged_index(sp, threadIdx.x);
+  if (threadIdx.x < 8 && i < sp.end) {
+    const float r = (FIRST ? 0.f : acc[i]) + load_grad1(g, i);
+    acc[i] = r;
+    if (SNAP) snap[i] = r;
   }
 }
 
-// ---------------------------------------------------------------------------------------------
-// accumulate for several replicas in one launch (blockIdx.y = pair index): same arithmetic per pair
-// as k_accumulate; for shards so small that the launch, not HBM, bounds a single accumulate.
-// ---------------------------------------------------------------------------------------------
+// accumulate for several replicas in one launch (blockIdx.y = pair index): same arithmetic per pair;
+// for shards so small that the launch, not HBM, bounds a single accumulate.  Lanes 0..7 of the first
+// workgroup of a pair also take the pair's ragged elements.
 template <typename G, int T, bool NT>
 __global__ __launch_bounds__(T) void k_accumulate_many(AccumulateManyArgs a, Span sp) {
+  typedef typename Grad4<G>::raw Raw;
   const int pair = blockIdx.y;
   float *acc = a.acc[pair];
   const G *g = static_cast<const G *>(a.grad[pair]);
-  const size_t ntiles = (sp.nvec + T - 1) / T;
+  f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
+  const Raw *g4 = reinterpret_cast<const Raw *>(g + sp.vbegin);
   if (a.first[pair])
-    accumulate_tiles<G, T, 1, NT, true, false>(acc, nullptr, g, sp, blockIdx.x, gridDim.x, ntiles);
+    accumulate_tile<G, T, 1, NT, true, false>(a4, nullptr, g4, sp.nvec);
   else
-    accumulate_tiles<G, T, 1, NT, false, false>(acc, nullptr, g, sp, blockIdx.x, gridDim.x, ntiles);
+    accumulate_tile<G, T, 1, NT, false, false>(a4, nullptr, g4, sp.nvec);
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t e = ragged_index(sp, threadIdx.x);
     if (e < sp.end) acc[e] = (a.first[pair] ? 0.f : acc[e]) + load_grad1(g, e);
@@ -183,69 +190,90 @@ __global__ __launch_bounds__(T) void k_accumulate_many(AccumulateManyArgs a, Spa
 // copy (snapshot and restore): dst[i] = src[i]
 // ---------------------------------------------------------------------------------------------
 template <int T, int U, bool NT>
-__device__ inline void copy_tiles(float *__restrict__ dst, const float *__restrict__ src, const Span &sp, size_t ntiles) {
-  f32x4 *d4 = reinterpret_cast<f32x4 *>(dst + sp.vbegin);
-  const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + sp.vbegin);
-  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(T * U) + threadIdx.x;
-    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
-      constexpr bool FULL = decltype(full)::value;
-      f32x4 x[U];
-      bool ok[U];
+__device__ inline void copy_tile(f32x4 *__restrict__ d4, const f32x4 *__restrict__ s4, size_t nvec) {
+  bool full;
+  const size_t base = tile_base<T, U>(nvec, &full);
+  on_tile(full, [&](auto is_full) {
+    constexpr bool FULL = decltype(is_full)::value;
+    f32x4 x[U];
+    bool ok[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
+    for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) x[u] = ld<NT>(s4 + base + size_t(T) * u);
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) x[u] = ld<NT>(s4 + base + size_t(T) * u);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) st<NT>(d4 + base + size_t(T) * u, x[u]);
-    });
-  }
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) st<NT>(d4 + base + size_t(T) * u, x[u]);
+  });
+}
+
+// RESTORE only names the instantiation (snapshot or rewind), so that a kernel trace tells the two apart.
+template <int T, int U, bool NT, bool RESTORE>
+__global__ __launch_bounds__(T) void k_copy(f32x4 *__restrict__ d4, const f32x4 *__restrict__ s4, size_t nvec) {
+  copy_tile<T, U, NT>(d4, s4, nvec);
+}
+
+// copy for several buffer pairs in one launch (blockIdx.y = pair): a snapshot or a rewind of every
+// survivor without a launch per replica; lanes 0..7 of a pair's first workgroup take its ragged elements.
+template <int T, int U, bool NT, bool RESTORE>
+__global__ __launch_bounds__(T) void k_copy_many(CopyManyArgs a, Span sp) {
+  float *dst = a.dst[blockIdx.y];
+  const float *src = a.src[blockIdx.y];
+  copy_tile<T, U, NT>(reinterpret_cast<f32x4 *>(dst + sp.vbegin), reinterpret_cast<const f32x4 *>(src + sp.vbegin), sp.nvec);
   if (blockIdx.x == 0 && threadIdx.x < 8) {
     const size_t i = ragged_index(sp, threadIdx.x);
     if (i < sp.end) dst[i] = src[i];
   }
 }
 
-template <int T, int U, bool NT>
-__global__ __launch_bounds__(T) void k_copy(float *__restrict__ dst, const float *__restrict__ src, Span sp,
-                                            size_t ntiles) {
-  copy_tiles<T, U, NT>(dst, src, sp, ntiles);
-}
-
-// copy for several buffer pairs in one launch (blockIdx.y = pair): a snapshot or a rewind of every
-// survivor without a launch per replica.
-template <int T, int U, bool NT>
-__global__ __launch_bounds__(T) void k_copy_many(CopyManyArgs a, Span sp, size_t ntiles) {
-  copy_tiles<T, U, NT>(a.dst[blockIdx.y], a.src[blockIdx.y], sp, ntiles);
+__global__ __launch_bounds__(64) void k_copy_ragged(float *__restrict__ dst, const float *__restrict__ src, Span sp) {
+  const size_t i = ragged_index(sp, threadIdx.x);
+  if (threadIdx.x < 8 && i < sp.end) dst[i] = src[i];
 }
 
 // ---------------------------------------------------------------------------------------------
 // reduce: out[i] = ((src0[i] + src1[i]) + ...) / divisor, ascending contributor order; in-place mode
-// also stores the undivided sum to every sum_dst buffer.  A workgroup walks the contributors one
-// after the other over its whole tile (U consecutive 1 KiB rows per contributor), two contributors'
-// loads in flight at a time, so each of its bursts reads one buffer contiguously; every element's
-// adds stay strictly left to right.
+// also stores the undivided sum to every sum_dst buffer.  A wavefront walks the contributors one after
+// the other over its tile, so each of its bursts reads one buffer contiguously; every element's adds
+// stay strictly left to right.  The pointers in ReduceArgs are the buffers' bases; `first` is the
+// element index of the range's first aligned vector.
 // ---------------------------------------------------------------------------------------------
-// sum[u] = contributor sum of the tile's vectors, for the lanes with ok[u].
-template <int T, int U, bool NT>
-__device__ inline void contributor_sum(const ReduceArgs &a, const Span &sp, size_t base, const bool (&ok)[U],
+// sum[u] = contributor sum of the tile's vectors, for the lanes with ok[u].  D = contributors whose loads
+// a wavefront has in flight at a time: 1 (each load waits for the one before: the least data in flight
+// per wavefront, best with many resident wavefronts) or 2 (pairs).  The order of the adds is the same.
+template <int T, int U, bool NT, int D>
+__device__ inline void contributor_sum(const ReduceArgs &a, size_t first, size_t base, const bool (&ok)[U],
                                        f32x4 (&sum)[U]) {
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int u = 0; u < U; ++u) sum[u] = zero;
   int r = 0;
   if (a.n_src > 0) {
-    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[0] + sp.vbegin) + base;
+    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[0] + first) + base;
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (ok[u]) sum[u] = ld<NT>(s0 + size_t(T) * u);
     r = 1;
   }
+  if (D == 1) {
+#pragma clang loop unroll(disable)
+    for (; r < a.n_src; ++r) {
+      const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + first) + base;
+      f32x4 t0[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) t0[u] = ld<NT>(s0 + size_t(T) * u);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) sum[u] = sum[u] + t0[u];
+      asm volatile("" ::: "memory");  // the next contributor's load is issued after this one has arrived
+    }
+    return;
+  }
   for (; r + 1 < a.n_src; r += 2) {
-    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
-    const f32x4 *s1 = reinterpret_cast<const f32x4 *>(a.src[r + 1] + sp.vbegin) + base;
+    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + first) + base;
+    const f32x4 *s1 = reinterpret_cast<const f32x4 *>(a.src[r + 1] + first) + base;
     f32x4 t0[U], t1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -258,55 +286,56 @@ __device__ inline void contributor_sum(const ReduceArgs &a, const Span &sp, size
       if (ok[u]) sum[u] = (sum[u] + t0[u]) + t1[u];
   }
   if (r < a.n_src) {
-    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + sp.vbegin) + base;
+    const f32x4 *s0 = reinterpret_cast<const f32x4 *>(a.src[r] + first) + base;
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (ok[u]) sum[u] = sum[u] + ld<NT>(s0 + size_t(T) * u);
   }
 }
 
-template <int T, int U, bool NT, bool INPLACE>
-__global__ __launch_bounds__(T) void k_reduce(ReduceArgs a, Span sp, size_t ntiles) {
-  f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
-  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(T * U) + threadIdx.x;
-    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
-      constexpr bool FULL = decltype(full)::value;
-      bool ok[U];
+template <int T, int U, bool NT, bool INPLACE, int D>
+__global__ __launch_bounds__(T) void k_reduce(ReduceArgs a, size_t first, size_t nvec) {
+  bool full;
+  const size_t base = tile_base<T, U>(nvec, &full);
+  on_tile(full, [&](auto is_full) {
+    constexpr bool FULL = decltype(is_full)::value;
+    bool ok[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
-      f32x4 sum[U];
-      contributor_sum<T, U, NT>(a, sp, base, ok, sum);
-      if (INPLACE) {
-        for (int d = 0; d < a.n_sum_dst; ++d) {
-          f32x4 *dd = reinterpret_cast<f32x4 *>(a.sum_dst[d] + sp.vbegin) + base;
+    for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
+    f32x4 sum[U];
+    contributor_sum<T, U, NT, D>(a, first, base, ok, sum);
+    if (INPLACE) {
+      for (int d = 0; d < a.n_sum_dst; ++d) {
+        f32x4 *dd = reinterpret_cast<f32x4 *>(a.sum_dst[d] + first) + base;
 #pragma unroll
-          for (int u = 0; u < U; ++u)
-            if (ok[u]) st<NT>(dd + size_t(T) * u, sum[u]);
-        }
+        for (int u = 0; u < U; ++u)
+          if (ok[u]) st<NT>(dd + size_t(T) * u, sum[u]);
       }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (ok[u]) {
-          f32x4 q;
-          q.x = sum[u].x / a.divisor;
-          q.y = sum[u].y / a.divisor;
-          q.z = sum[u].z / a.divisor;
-          q.w = sum[u].w / a.divisor;
-          st<NT>(o4 + base + size_t(T) * u, q);
-        }
-      }
-    });
-  }
-  if (blockIdx.x == 0 && threadIdx.x < 8) {
-    const size_t i = ragged_index(sp, threadIdx.x);
-    if (i < sp.end) {
-      float sum = 0.f;
-      for (int r = 0; r < a.n_src; ++r) sum = (r == 0) ? a.src[r][i] : sum + a.src[r][i];
-      if (INPLACE)
-        for (int d = 0; d < a.n_sum_dst; ++d) a.sum_dst[d][i] = sum;
-      a.out[i] = sum / a.divisor;
     }
+    f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + first) + base;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (ok[u]) {
+        f32x4 q;
+        q.x = sum[u].x / a.divisor;
+        q.y = sum[u].y / a.divisor;
+        q.z = sum[u].z / a.divisor;
+        q.w = sum[u].w / a.divisor;
+        st<NT>(o4 + size_t(T) * u, q);
+      }
+    }
+  });
+}
+
+template <bool INPLACE>
+__global__ __launch_bounds__(64) void k_reduce_ragged(ReduceArgs a, Span sp) {
+  const size_t i = ragged_index(sp, threadIdx.x);
+  if (threadIdx.x < 8 && i < sp.end) {
+    float sum = 0.f;
+    for (int r = 0; r < a.n_src; ++r) sum = (r == 0) ? a.src[r][i] : sum + a.src[r][i];
+    if (INPLACE)
+      for (int d = 0; d < a.n_sum_dst; ++d) a.sum_dst[d][i] = sum;
+    a.out[i] = sum / a.divisor;
   }
 }
 
@@ -351,84 +380,98 @@ __device__ inline u32x2 pack_bf16x4(f32x4 p) {
   return w;
 }
 
-// Loads p, m, v of the tile, applies the update with gradient gv, stores p, m, v (and the bf16 copy).
-template <int T, int U, bool NT, bool BF16OUT>
-__device__ inline void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restrict__ m4, f32x4 *__restrict__ v4,
-                                 u32x2 *__restrict__ b2, size_t base, const bool (&ok)[U], const f32x4 (&gv)[U],
-                                 const AdamArgs &h) {
+// Device pointers of the optimiser state, advanced to the range's first aligned vector.
+struct AdamPtrs {
+  f32x4 *p4, *m4, *v4;
+  u32x2 *b2;  // bf16 copy of the parameters or nullptr
+};
+
+// The tile's p, m, v.
+template <int U>
+struct AdamTile {
   f32x4 pv[U], mv[U], vv[U];
+};
+template <int T, int U, bool NT>
+__device__ inline void adam_load(const AdamPtrs &s, size_t base, const bool (&ok)[U], AdamTile<U> &x) {
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    if (ok[u]) pv[u] = ld<NT>(p4 + base + size_t(T) * u);
+    if (ok[u]) x.pv[u] = ld<NT>(s.p4 + base + size_t(T) * u);
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    if (ok[u]) mv[u] = ld<NT>(m4 + base + size_t(T) * u);
+    if (ok[u]) x.mv[u] = ld<NT>(s.m4 + base + size_t(T) * u);
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    if (ok[u]) vv[u] = ld<NT>(v4 + base + size_t(T) * u);
+    if (ok[u]) x.vv[u] = ld<NT>(s.v4 + base + size_t(T) * u);
+}
+// Applies the update with gradient gv to the loaded tile and stores p, m, v (and the bf16 copy).
+template <int T, int U, bool NT, bool BF16OUT>
+__device__ inline void adam_update_store(const AdamPtrs &s, size_t base, const bool (&ok)[U], AdamTile<U> &x,
+                                         const f32x4 (&gv)[U], const AdamArgs &h) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (ok[u]) {
 #pragma unroll
       for (int l = 0; l < 4; ++l) {
-        float pp = pv[u][l], mm = mv[u][l], v1 = vv[u][l];
+        float pp = x.pv[u][l], mm = x.mv[u][l], v1 = x.vv[u][l];
         adam1(pp, mm, v1, gv[u][l], h);
-        pv[u][l] = pp;
-        mv[u][l] = mm;
-        vv[u][l] = v1;
+        x.pv[u][l] = pp;
+        x.mv[u][l] = mm;
+        x.vv[u][l] = v1;
       }
     }
   }
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    if (ok[u]) st<NT>(p4 + base + size_t(T) * u, pv[u]);
+    if (ok[u]) st<NT>(s.p4 + base + size_t(T) * u, x.pv[u]);
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    if (ok[u]) st<NT>(m4 + base + size_t(T) * u, mv[u]);
+    if (ok[u]) st<NT>(s.m4 + base + size_t(T) * u, x.mv[u]);
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    if (ok[u]) st<NT>(v4 + base + size_t(T) * u, vv[u]);
+    if (ok[u]) st<NT>(s.v4 + base + size_t(T) * u, x.vv[u]);
   if (BF16OUT) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (ok[u]) st<NT>(b2 + base + size_t(T) * u, pack_bf16x4(pv[u]));
+      if (ok[u]) st<NT>(s.b2 + base + size_t(T) * u, pack_bf16x4(x.pv[u]));
   }
 }
 
-template <int T, int U, bool NT, bool BF16OUT>
-__global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__restrict__ m,
-                                                    float *__restrict__ v, const float *__restrict__ g,
-                                                    uint16_t *__restrict__ pb, size_t n, AdamArgs h_arg,
-                                                    const AdamArgs *h_dev, size_t ntiles) {
+// DEV: the step's constants are read from device memory (written by k_adam_prologue) instead of the
+// kernel arguments; a template parameter so that the argument path keeps its constants in scalar registers.
+template <int T, int U, bool NT, bool BF16OUT, bool DEV>
+__global__ __launch_bounds__(T) void k_adamw(AdamPtrs s, const f32x4 *__restrict__ g4, size_t nvec, AdamArgs h_arg,
+                                             const AdamArgs *__restrict__ h_dev) {
+  const AdamArgs h = DEV ? *h_dev : h_arg;
+  bool full;
+  const size_t base = tile_base<T, U>(nvec, &full);
+  on_tile(full, [&](auto is_full) {
+    constexpr bool FULL = decltype(is_full)::value;
+    bool ok[U];
+    f32x4 gv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) gv[u] = ld<NT>(g4 + base + size_t(T) * u);
+    AdamTile<U> x;
+    adam_load<T, U, NT>(s, base, ok, x);
+    adam_update_store<T, U, NT, BF16OUT>(s, base, ok, x, gv, h);
+  });
+}
+
+// Elements [begin, end) one per lane (the tail of a buffer whose length is not a multiple of four).
+__global__ __launch_bounds__(64) void k_adamw_ragged(float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
+                                                     const float *__restrict__ g, uint16_t *__restrict__ pb, size_t begin,
+                                                     size_t end, AdamArgs h_arg, const AdamArgs *h_dev) {
   const AdamArgs h = h_dev ? *h_dev : h_arg;
-  const size_t nvec = n / 4;
-  f32x4 *p4 = reinterpret_cast<f32x4 *>(p), *m4 = reinterpret_cast<f32x4 *>(m), *v4 = reinterpret_cast<f32x4 *>(v);
-  const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
-  u32x2 *b2 = reinterpret_cast<u32x2 *>(pb);
-  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(T * U) + threadIdx.x;
-    on_tile((tile + 1) * size_t(T * U) <= nvec, [&](auto full) {
-      constexpr bool FULL = decltype(full)::value;
-      bool ok[U];
-      f32x4 gv[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) gv[u] = ld<NT>(g4 + base + size_t(T) * u);
-      adam_tile<T, U, NT, BF16OUT>(p4, m4, v4, b2, base, ok, gv, h);
-    });
-  }
-  if (blockIdx.x == 0 && threadIdx.x < 4) {
-    const size_t i = nvec * 4 + threadIdx.x;
-    if (i < n) {
-      float pp = p[i], mm = m[i], vv = v[i];
-      adam1(pp, mm, vv, g[i], h);
-      p[i] = pp;
-      m[i] = mm;
-      v[i] = vv;
-      if (BF16OUT) pb[i] = (uint16_t)f32_to_bf16_rne(pp);
-    }
+  const size_t i = begin + threadIdx.x;
+  if (i < end) {
+    float pp = p[i], mm = m[i], vv = v[i];
+    adam1(pp, mm, vv, g[i], h);
+    p[i] = pp;
+    m[i] = mm;
+    v[i] = vv;
+    if (pb) pb[i] = (uint16_t)f32_to_bf16_rne(pp);
   }
 }
 
@@ -437,52 +480,57 @@ __global__ __launch_bounds__(T) void k_adamw(float *__restrict__ p, float *__res
 // update of k_adamw in one pass; the gradient goes to HBM only if WRITE_GRAD.  4 R_c + 24 (+4) bytes
 // per element.
 // ---------------------------------------------------------------------------------------------
-template <int T, int U, bool NT, bool WRITE_GRAD, bool BF16OUT>
-__global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, float *__restrict__ p, float *__restrict__ m,
-                                                    float *__restrict__ v, uint16_t *__restrict__ pb, Span sp,
-                                                    AdamArgs h_arg, const AdamArgs *h_dev, size_t ntiles) {
-  const AdamArgs h = h_dev ? *h_dev : h_arg;
-  f32x4 *p4 = reinterpret_cast<f32x4 *>(p + sp.vbegin), *m4 = reinterpret_cast<f32x4 *>(m + sp.vbegin);
-  f32x4 *v4 = reinterpret_cast<f32x4 *>(v + sp.vbegin), *o4 = reinterpret_cast<f32x4 *>(a.out + sp.vbegin);
-  u32x2 *b2 = reinterpret_cast<u32x2 *>(pb + sp.vbegin);
-  for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const size_t base = tile * size_t(T * U) + threadIdx.x;
-    on_tile((tile + 1) * size_t(T * U) <= sp.nvec, [&](auto full) {
-      constexpr bool FULL = decltype(full)::value;
-      bool ok[U];
+// EARLY: the loads of p, m, v are issued before the contributor walk instead of after it.
+template <int T, int U, bool NT, bool WRITE_GRAD, bool BF16OUT, int D, bool DEV, bool EARLY>
+__global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, AdamPtrs s, size_t first, size_t nvec, AdamArgs h_arg,
+                                                    const AdamArgs *__restrict__ h_dev) {
+  const AdamArgs h = DEV ? *h_dev : h_arg;
+  bool full;
+  const size_t base = tile_base<T, U>(nvec, &full);
+  on_tile(full, [&](auto is_full) {
+    constexpr bool FULL = decltype(is_full)::value;
+    bool ok[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < sp.nvec;
-      f32x4 sum[U];
-      contributor_sum<T, U, NT>(a, sp, base, ok, sum);
+    for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
+    f32x4 sum[U];
+    AdamTile<U> x;
+    if (EARLY) adam_load<T, U, NT>(s, base, ok, x);  // in flight during the walk
+    contributor_sum<T, U, NT, D>(a, first, base, ok, sum);
+    if (!EARLY) adam_load<T, U, NT>(s, base, ok, x);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        sum[u].x = sum[u].x / a.divisor;
-        sum[u].y = sum[u].y / a.divisor;
-        sum[u].z = sum[u].z / a.divisor;
-        sum[u].w = sum[u].w / a.divisor;
-      }
-      adam_tile<T, U, NT, BF16OUT>(p4, m4, v4, b2, base, ok, sum, h);
-      if (WRITE_GRAD) {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-          if (ok[u]) st<NT>(o4 + base + size_t(T) * u, sum[u]);
-      }
-    });
-  }
-  if (blockIdx.x == 0 && threadIdx.x < 8) {
-    const size_t e = ragged_index(sp, threadIdx.x);
-    if (e < sp.end) {
-      float sum = 0.f;
-      for (int r = 0; r < a.n_src; ++r) sum = (r == 0) ? a.src[r][e] : sum + a.src[r][e];
-      const float q = sum / a.divisor;
-      float pp = p[e], mm = m[e], v1 = v[e];
-      adam1(pp, mm, v1, q, h);
-      p[e] = pp;
-      m[e] = mm;
-      v[e] = v1;
-      if (WRITE_GRAD) a.out[e] = q;
-      if (BF16OUT) pb[e] = (uint16_t)f32_to_bf16_rne(pp);
+    for (int u = 0; u < U; ++u) {
+      sum[u].x = sum[u].x / a.divisor;
+      sum[u].y = sum[u].y / a.divisor;
+      sum[u].z = sum[u].z / a.divisor;
+      sum[u].w = sum[u].w / a.divisor;
     }
+    adam_update_store<T, U, NT, BF16OUT>(s, base, ok, x, sum, h);
+    if (WRITE_GRAD) {
+      f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out + first) + base;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) st<NT>(o4 + size_t(T) * u, sum[u]);
+    }
+  });
+}
+
+template <bool WRITE_GRAD>
+__global__ __launch_bounds__(64) void k_reduce_adamw_ragged(ReduceArgs a, float *__restrict__ p, float *__restrict__ m,
+                                                            float *__restrict__ v, uint16_t *__restrict__ pb, Span sp,
+                                                            AdamArgs h_arg, const AdamArgs *h_dev) {
+  const AdamArgs h = h_dev ? *h_dev : h_arg;
+  const size_t e = ragged_index(sp, threadIdx.x);
+  if (threadIdx.x < 8 && e < sp.end) {
+    float sum = 0.f;
+    for (int r = 0; r < a.n_src; ++r) sum = (r == 0) ? a.src[r][e] : sum + a.src[r][e];
+    const float q = sum / a.divisor;
+    float pp = p[e], mm = m[e], v1 = v[e];
+    adam1(pp, mm, v1, q, h);
+    p[e] = pp;
+    m[e] = mm;
+    v[e] = v1;
+    if (WRITE_GRAD) a.out[e] = q;
+    if (pb) pb[e] = (uint16_t)f32_to_bf16_rne(pp);
   }
 }
 
@@ -514,34 +562,45 @@ __global__ __launch_bounds__(256) void k_compare_clear(CompareResult *out) {
   }
 }
 
-__global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, const float *__restrict__ ref, size_t n,
-                                                 CompareResult *out) {
+struct CompareFold {
   uint64_t mism = 0, nans = 0, cx = 0, cr = 0;
   uint32_t mdiff = 0, mref = 0;  // bit patterns of non-negative floats order like the floats
-  for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += size_t(gridDim.x) * 256) {
-    const float a = x[i], b = ref[i];
+  __device__ inline void take(float a, float b, size_t i) {
     const uint32_t ab = __builtin_bit_cast(uint32_t, a), bb = __builtin_bit_cast(uint32_t, b);
     mism += ab != bb;
     cx += uint64_t(ab) * (2 * uint64_t(i) + 1);
     cr += uint64_t(bb) * (2 * uint64_t(i) + 1);
     if (a != a || b != b) {
       nans += 1;
-    } else if (ab != bb) {  // equal bits differ by nothing (also for two equal infinities, whose difference is a NaN)
-      const uint32_t d = __builtin_bit_cast(uint32_t, __builtin_fabsf(a - b));  // +Inf for opposite infinities
-      const uint32_t r = bb & 0x7FFFFFFFu;
-      mdiff = d > mdiff ? d : mdiff;
-      mref = r > mref ? r : mref;
     } else {
       const uint32_t r = bb & 0x7FFFFFFFu;
       mref = r > mref ? r : mref;
+      if (ab != bb) {  // equal bits differ by nothing (also two equal infinities, whose difference is a NaN)
+        const uint32_t d = __builtin_bit_cast(uint32_t, __builtin_fabsf(a - b));  // +Inf for opposite infinities
+        mdiff = d > mdiff ? d : mdiff;
+      }
     }
   }
-  mism = wave_sum_u64(mism);
-  nans = wave_sum_u64(nans);
-  cx = wave_sum_u64(cx);
-  cr = wave_sum_u64(cr);
-  mdiff = wave_max_u32(mdiff);
-  mref = wave_max_u32(mref);
+};
+
+// Two streams read with 128-bit loads, nothing written but six atomics per wavefront: also the library's
+// read-only bandwidth probe.
+__global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, const float *__restrict__ ref, size_t n,
+                                                 CompareResult *out) {
+  CompareFold f;
+  const size_t nvec = n / 4;
+  const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x), *r4 = reinterpret_cast<const f32x4 *>(ref);
+  for (size_t v = size_t(blockIdx.x) * 256 + threadIdx.x; v < nvec; v += size_t(gridDim.x) * 256) {
+    const f32x4 a = __builtin_nontemporal_load(x4 + v), b = __builtin_nontemporal_load(r4 + v);
+#pragma unroll
+    for (int l = 0; l < 4; ++l) f.take(a[l], b[l], 4 * v + l);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < 4) {
+    const size_t i = nvec * 4 + threadIdx.x;
+    if (i < n) f.take(x[i], ref[i], i);
+  }
+  const uint64_t mism = wave_sum_u64(f.mism), nans = wave_sum_u64(f.nans), cx = wave_sum_u64(f.cx), cr = wave_sum_u64(f.cr);
+  const uint32_t mdiff = wave_max_u32(f.mdiff), mref = wave_max_u32(f.mref);
   if ((threadIdx.x & 63) == 0) {
     atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_mismatch), (unsigned long long)mism);
     atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_nan), (unsigned long long)nans);
@@ -555,14 +614,11 @@ __global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, co
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-static bool grid_for(size_t nvec, int T, int U, unsigned *grid, size_t *ntiles) {
-  size_t tiles = (nvec + size_t(T) * U - 1) / (size_t(T) * U);
-  *ntiles = tiles;
-  size_t g = tiles ? tiles : 1;
-  int cap = tuning().grid_cap;
-  if (cap > 0 && g > size_t(cap)) g = size_t(cap);
-  if (g > 0x7FFFFFFFull) return false;
-  *grid = (unsigned)g;
+// One tile of T * U vectors per workgroup.
+static bool grid_for(size_t nvec, int T, int U, unsigned *grid) {
+  const size_t tiles = (nvec + size_t(T) * U - 1) / (size_t(T) * U);
+  if (tiles > 0x7FFFFFFFull) return false;
+  *grid = (unsigned)tiles;
   return true;
 }
 
@@ -610,32 +666,34 @@ hipError_t launch_accumulate(float *acc, float *snap, const void *grad, bool gra
   const int Uv = sh.vecs, Tv = tuning().threads;
   const unsigned lds = lds_share(sh.waves, Tv);
   unsigned grid;
-  size_t ntiles;
-  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
-  const int xc = tuning().xcd_chunked && tuning().grid_cap == 0 && ntiles >= 64 ? 1 : 0;
-  if (xc) grid = (unsigned)(((ntiles + 7) / 8) * 8);
-  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
-    constexpr int T = decltype(t)::value, U = decltype(u)::value;
-    constexpr bool NT = decltype(nt)::value;
-    auto go = [&](auto gptr, auto is_first, auto with_snap) {
-      using GT = std::remove_cv_t<std::remove_pointer_t<decltype(gptr)>>;
-      hipLaunchKernelGGL((k_accumulate<GT, T, U, NT, decltype(is_first)::value, decltype(with_snap)::value>), dim3(grid),
-                         dim3(T), lds, s, acc, snap, gptr, sp, ntiles, xc);
+  if (!grid_for(sp.nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
+  f32x4 *a4 = reinterpret_cast<f32x4 *>(acc + sp.vbegin);
+  f32x4 *s4 = snap ? reinterpret_cast<f32x4 *>(snap + sp.vbegin) : nullptr;
+  auto pick = [&](auto gptr) {  // gptr: typed base of the gradient
+    using GT = std::remove_cv_t<std::remove_pointer_t<decltype(gptr)>>;
+    using Raw = typename Grad4<GT>::raw;
+    const Raw *g4 = reinterpret_cast<const Raw *>(gptr + sp.vbegin);
+    auto go = [&](auto is_first, auto with_snap) {
+      constexpr bool F = decltype(is_first)::value, SN = decltype(with_snap)::value;
+      if (grid)
+        with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+          hipLaunchKernelGGL((k_accumulate<GT, decltype(t)::value, decltype(u)::value, decltype(nt)::value, F, SN>),
+                             dim3(grid), dim3(decltype(t)::value), lds, s, a4, s4, g4, sp.nvec);
+        });
+      if (ragged(sp)) hipLaunchKernelGGL((k_accumulate_ragged<GT, F, SN>), dim3(1), dim3(64), 0, s, acc, snap, gptr, sp);
     };
-    auto pick = [&](auto gptr) {
-      if (first) {
-        if (snap) go(gptr, std::true_type{}, std::true_type{});
-        else go(gptr, std::true_type{}, std::false_type{});
-      } else {
-        if (snap) go(gptr, std::false_type{}, std::true_type{});
-        else go(gptr, std::false_type{}, std::false_type{});
-      }
-    };
-    if (grad_is_bf16)
-      pick(static_cast<const uint16_t *>(grad));
-    else
-      pick(static_cast<const float *>(grad));
-  });
+    if (first) {
+      if (snap) go(std::true_type{}, std::true_type{});
+      else go(std::true_type{}, std::false_type{});
+    } else {
+      if (snap) go(std::false_type{}, std::true_type{});
+      else go(std::false_type{}, std::false_type{});
+    }
+  };
+  if (grad_is_bf16)
+    pick(static_cast<const uint16_t *>(grad));
+  else
+    pick(static_cast<const float *>(grad));
   return hipGetLastError();
 }
 
@@ -657,36 +715,46 @@ hipError_t launch_accumulate_many(const AccumulateManyArgs &a, int n_pairs, bool
   return hipGetLastError();
 }
 
-hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, hipStream_t s) {
+hipError_t launch_copy(float *dst, const float *src, size_t begin, size_t end, bool restore, hipStream_t s) {
   if (begin >= end) return hipSuccess;
   const Span sp = make_span(begin, end);
   const Shape sh = tuning().shape[kCopy];
   const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
-  size_t ntiles;
-  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
-  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
-    constexpr int T = decltype(t)::value, U = decltype(u)::value;
-    constexpr bool NT = decltype(nt)::value;
-    hipLaunchKernelGGL((k_copy<T, U, NT>), dim3(grid), dim3(T), lds_share(sh.waves, T), s, dst, src, sp, ntiles);
-  });
+  if (!grid_for(sp.nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
+  if (grid)
+    with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+      constexpr int T = decltype(t)::value, U = decltype(u)::value;
+      f32x4 *d4 = reinterpret_cast<f32x4 *>(dst + sp.vbegin);
+      const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + sp.vbegin);
+      if (restore)
+        hipLaunchKernelGGL((k_copy<T, U, decltype(nt)::value, true>), dim3(grid), dim3(T), lds_share(sh.waves, T), s, d4, s4,
+                           sp.nvec);
+      else
+        hipLaunchKernelGGL((k_copy<T, U, decltype(nt)::value, false>), dim3(grid), dim3(T), lds_share(sh.waves, T), s, d4, s4,
+                           sp.nvec);
+    });
+  if (ragged(sp)) hipLaunchKernelGGL(k_copy_ragged, dim3(1), dim3(64), 0, s, dst, src, sp);
   return hipGetLastError();
 }
 
-hipError_t launch_copy_many(const CopyManyArgs &a, int n_pairs, size_t begin, size_t end, hipStream_t s) {
+hipError_t launch_copy_many(const CopyManyArgs &a, int n_pairs, size_t begin, size_t end, bool restore, hipStream_t s) {
   if (begin >= end || n_pairs <= 0) return hipSuccess;
   if (n_pairs > kMaxReplicas) return hipErrorInvalidConfiguration;
   const Span sp = make_span(begin, end);
   const Shape sh = tuning().shape[kCopy];
   const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
-  size_t ntiles;
-  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  if (!grid_for(sp.nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
+  if (!grid) grid = 1;  // the ragged elements ride on workgroup 0 of every pair
   with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
     constexpr int T = decltype(t)::value, U = decltype(u)::value;
-    constexpr bool NT = decltype(nt)::value;
-    hipLaunchKernelGGL((k_copy_many<T, U, NT>), dim3(grid, (unsigned)n_pairs), dim3(T), lds_share(sh.waves, T), s, a, sp,
-                       ntiles);
+    if (restore)
+      hipLaunchKernelGGL((k_copy_many<T, U, decltype(nt)::value, true>), dim3(grid, (unsigned)n_pairs), dim3(T),
+                         lds_share(sh.waves, T), s, a, sp);
+    else
+      hipLaunchKernelGGL((k_copy_many<T, U, decltype(nt)::value, false>), dim3(grid, (unsigned)n_pairs), dim3(T),
+                         lds_share(sh.waves, T), s, a, sp);
   });
   return hipGetLastError();
 }
@@ -697,18 +765,43 @@ hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStrea
   const Shape sh = tuning().shape[kReduce];
   const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
-  size_t ntiles;
-  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
+  if (!grid_for(sp.nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
   const bool inplace = a.n_sum_dst > 0;
-  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
-    constexpr int T = decltype(t)::value, U = decltype(u)::value;
-    constexpr bool NT = decltype(nt)::value;
-    const unsigned lds = lds_share(sh.waves, T);
-    if (inplace)
-      hipLaunchKernelGGL((k_reduce<T, U, NT, true>), dim3(grid), dim3(T), lds, s, a, sp, ntiles);
-    else
-      hipLaunchKernelGGL((k_reduce<T, U, NT, false>), dim3(grid), dim3(T), lds, s, a, sp, ntiles);
-  });
+  if (grid)
+    with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+      constexpr int T = decltype(t)::value, U = decltype(u)::value;
+      constexpr bool NT = decltype(nt)::value;
+      const unsigned lds = lds_share(sh.waves, T);
+      auto go = [&](auto ip, auto d) {
+        hipLaunchKernelGGL((k_reduce<T, U, NT, decltype(ip)::value, decltype(d)::value>), dim3(grid), dim3(T), lds, s, a,
+                           sp.vbegin, sp.nvec);
+      };
+      auto with_d = [&](auto ip) {
+        if (sh.depth == 1) go(ip, Int<1>{});
+        else go(ip, Int<2>{});
+      };
+      if (inplace) with_d(std::true_type{});
+      else with_d(std::false_type{});
+    });
+  if (ragged(sp)) {
+    if (inplace) hipLaunchKernelGGL(k_reduce_ragged<true>, dim3(1), dim3(64), 0, s, a, sp);
+    else hipLaunchKernelGGL(k_reduce_ragged<false>, dim3(1), dim3(64), 0, s, a, sp);
+  }
+  return hipGetLastError();
+}
+
+__global__ void k_clear_step_state(StepState *st) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    st->step = 0;
+    st->beta1_pow = 1.0;
+    st->beta2_pow = 1.0;
+    st->args = AdamArgs{};
+    st->reserved = 0;
+  }
+}
+
+hipError_t launch_clear_step_state(StepState *st, hipStream_t s) {
+  hipLaunchKernelGGL(k_clear_step_state, dim3(1), dim3(64), 0, s, st);
   return hipGetLastError();
 }
 
@@ -718,25 +811,43 @@ hipError_t launch_adam_prologue(StepState *st, float lr, float beta1, float beta
   return hipGetLastError();
 }
 
+static AdamPtrs adam_ptrs(float *p, float *m, float *v, uint16_t *p_bf16, size_t first) {
+  AdamPtrs q;
+  q.p4 = reinterpret_cast<f32x4 *>(p + first);
+  q.m4 = reinterpret_cast<f32x4 *>(m + first);
+  q.v4 = reinterpret_cast<f32x4 *>(v + first);
+  q.b2 = p_bf16 ? reinterpret_cast<u32x2 *>(p_bf16 + first) : nullptr;
+  return q;
+}
+
 hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, const AdamArgs &h,
                         const AdamArgs *device_args, hipStream_t s) {
   if (n == 0) return hipSuccess;
   const Shape sh = tuning().shape[kAdamw];
   const int Uv = sh.vecs, Tv = tuning().threads;
+  const size_t nvec = n / 4;
   unsigned grid;
-  size_t ntiles;
-  if (!grid_for(n / 4, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
-  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
-    constexpr int T = decltype(t)::value, U = decltype(u)::value;
-    constexpr bool NT = decltype(nt)::value;
-    const unsigned lds = lds_share(sh.waves, T);
-    if (p_bf16)
-      hipLaunchKernelGGL((k_adamw<T, U, NT, true>), dim3(grid), dim3(T), lds, s, p, m, v, g, p_bf16, n, h, device_args,
-                         ntiles);
-    else
-      hipLaunchKernelGGL((k_adamw<T, U, NT, false>), dim3(grid), dim3(T), lds, s, p, m, v, g, p_bf16, n, h, device_args,
-                         ntiles);
-  });
+  if (!grid_for(nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
+  const AdamPtrs q = adam_ptrs(p, m, v, p_bf16, 0);
+  if (grid)
+    with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+      constexpr int T = decltype(t)::value, U = decltype(u)::value;
+      constexpr bool NT = decltype(nt)::value;
+      const unsigned lds = lds_share(sh.waves, T);
+      const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
+      auto go = [&](auto bf, auto dev) {
+        hipLaunchKernelGGL((k_adamw<T, U, NT, decltype(bf)::value, decltype(dev)::value>), dim3(grid), dim3(T), lds, s, q,
+                           g4, nvec, h, device_args);
+      };
+      auto with_dev = [&](auto bf) {
+        if (device_args) go(bf, std::true_type{});
+        else go(bf, std::false_type{});
+      };
+      if (p_bf16) with_dev(std::true_type{});
+      else with_dev(std::false_type{});
+    });
+  if (nvec * 4 != n)
+    hipLaunchKernelGGL(k_adamw_ragged, dim3(1), dim3(64), 0, s, p, m, v, g, p_bf16, nvec * 4, n, h, device_args);
   return hipGetLastError();
 }
 
@@ -748,31 +859,53 @@ hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v
   const Shape sh = tuning().shape[kReduceAdamw];
   const int Uv = sh.vecs, Tv = tuning().threads;
   unsigned grid;
-  size_t ntiles;
-  if (!grid_for(sp.nvec, Tv, Uv, &grid, &ntiles)) return hipErrorInvalidConfiguration;
-  with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
-    constexpr int T = decltype(t)::value, U = decltype(u)::value;
-    constexpr bool NT = decltype(nt)::value;
-    const unsigned lds = lds_share(sh.waves, T);
-    auto go = [&](auto wg, auto bf) {
-      hipLaunchKernelGGL((k_reduce_adamw<T, U, NT, decltype(wg)::value, decltype(bf)::value>), dim3(grid), dim3(T), lds,
-                         s, a, p, m, v, p_bf16, sp, h, device_args, ntiles);
-    };
-    auto with_bf = [&](auto wg) {
-      if (p_bf16) go(wg, std::true_type{});
-      else go(wg, std::false_type{});
-    };
-    if (write_grad) with_bf(std::true_type{});
-    else with_bf(std::false_type{});
-  });
+  if (!grid_for(sp.nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
+  const AdamPtrs q = adam_ptrs(p, m, v, p_bf16, sp.vbegin);
+  if (grid)
+    with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
+      constexpr int T = decltype(t)::value, U = decltype(u)::value;
+      constexpr bool NT = decltype(nt)::value;
+      const unsigned lds = lds_share(sh.waves, T);
+      auto go = [&](auto wg, auto bf, auto d, auto dev, auto early) {
+        hipLaunchKernelGGL((k_reduce_adamw<T, U, NT, decltype(wg)::value, decltype(bf)::value, decltype(d)::value / 10,
+                                           decltype(dev)::value, decltype(early)::value>),
+                           dim3(grid), dim3(T), lds, s, a, q, sp.vbegin, sp.nvec, h, device_args);
+      };
+      auto with_dev = [&](auto wg, auto bf, auto d) {
+        constexpr bool early = decltype(d)::value % 10 != 0;
+        if (device_args) go(wg, bf, d, std::true_type{}, std::integral_constant<bool, early>{});
+        else go(wg, bf, d, std::false_type{}, std::integral_constant<bool, early>{});
+      };
+      auto with_d = [&](auto wg, auto bf) {  // depth: 1, 2 = contributors in flight; +2 = p, m, v loaded before the walk
+        switch (sh.depth) {
+          case 1: with_dev(wg, bf, Int<10>{}); break;
+          case 3: with_dev(wg, bf, Int<11>{}); break;
+          case 4: with_dev(wg, bf, Int<21>{}); break;
+          default: with_dev(wg, bf, Int<20>{}); break;
+        }
+      };
+      auto with_bf = [&](auto wg) {
+        if (p_bf16) with_d(wg, std::true_type{});
+        else with_d(wg, std::false_type{});
+      };
+      if (write_grad) with_bf(std::true_type{});
+      else with_bf(std::false_type{});
+    });
+  if (ragged(sp)) {
+    if (write_grad)
+      hipLaunchKernelGGL(k_reduce_adamw_ragged<true>, dim3(1), dim3(64), 0, s, a, p, m, v, p_bf16, sp, h, device_args);
+    else
+      hipLaunchKernelGGL(k_reduce_adamw_ragged<false>, dim3(1), dim3(64), 0, s, a, p, m, v, p_bf16, sp, h, device_args);
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_compare(const float *x, const float *ref, size_t n, CompareResult *out, hipStream_t s) {
   hipLaunchKernelGGL(k_compare_clear, dim3(1), dim3(256), 0, s, out);
   if (n > 0) {
-    size_t blocks = (n + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    size_t blocks = (n / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 256 * 32) blocks = 256 * 32;
     hipLaunchKernelGGL(k_compare, dim3((unsigned)blocks), dim3(256), 0, s, x, ref, n, out);
   }
   return hipGetLastError();

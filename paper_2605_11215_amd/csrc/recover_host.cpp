@@ -426,8 +426,8 @@ int recover_snapshot(recover_ctx *c, int replica, int tb, int te, void *stream) 
     ++n;
   }
   if (!c->host_only) {  // one launch whatever the number of replicas
-    hipError_t he = n == 1 ? recover::launch_copy(a.dst[0], a.src[0], (size_t)c->off[tb], (size_t)c->off[te], (hipStream_t)stream)
-                           : recover::launch_copy_many(a, n, (size_t)c->off[tb], (size_t)c->off[te], (hipStream_t)stream);
+    hipError_t he = n == 1 ? recover::launch_copy(a.dst[0], a.src[0], (size_t)c->off[tb], (size_t)c->off[te], false, (hipStream_t)stream)
+                           : recover::launch_copy_many(a, n, (size_t)c->off[tb], (size_t)c->off[te], false, (hipStream_t)stream);
     if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "snapshot: %s", hipGetErrorString(he));
   }
   for (int r = 0; r < c->W; ++r) {
@@ -503,8 +503,8 @@ int recover_restore(recover_ctx *c, int replica, int stale_only, void *stream) {
         }
         int e = b;
         while (e < c->T && pk[e]) ++e;
-        hipError_t he = n == 1 ? recover::launch_copy(a.dst[0], a.src[0], (size_t)c->off[b], (size_t)c->off[e], (hipStream_t)stream)
-                               : recover::launch_copy_many(a, n, (size_t)c->off[b], (size_t)c->off[e], (hipStream_t)stream);
+        hipError_t he = n == 1 ? recover::launch_copy(a.dst[0], a.src[0], (size_t)c->off[b], (size_t)c->off[e], true, (hipStream_t)stream)
+                               : recover::launch_copy_many(a, n, (size_t)c->off[b], (size_t)c->off[e], true, (hipStream_t)stream);
         if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "restore: %s", hipGetErrorString(he));
         b = e;
       }
@@ -756,16 +756,16 @@ struct StepConsts {
   const recover::AdamArgs *device_args;
   double next_beta1_pow, next_beta2_pow;
 };
-static int prepare_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
-                        hipStream_t stream, StepConsts *k, const char *who) {
+static int prepare_step(recover_ctx *c, recover::StepState *device_state, float lr, float beta1, float beta2, float eps,
+                        float weight_decay, hipStream_t stream, StepConsts *k, const char *who) {
   k->next_beta1_pow = c->beta1_pow;
   k->next_beta2_pow = c->beta2_pow;
   k->args = recover::next_adam_args(k->next_beta1_pow, k->next_beta2_pow, lr, beta1, beta2, eps, weight_decay);
   k->device_args = nullptr;
-  if (c->step_state && !c->host_only) {
-    hipError_t he = recover::launch_adam_prologue(c->step_state, lr, beta1, beta2, eps, weight_decay, stream);
+  if (device_state && !c->host_only) {
+    hipError_t he = recover::launch_adam_prologue(device_state, lr, beta1, beta2, eps, weight_decay, stream);
     if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "%s: %s", who, hipGetErrorString(he));
-    k->device_args = &c->step_state->args;
+    k->device_args = &device_state->args;
   }
   return RECOVER_OK;
 }
@@ -779,9 +779,8 @@ static void commit_iteration(recover_ctx *c, const StepConsts &k) {
   open_iteration(c);
 }
 
-int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
-                       void *stream) {
-  if (!c) return RECOVER_ERR_ARG;
+static int adamw_step_impl(recover_ctx *c, recover::StepState *device_state, bool clear_state, float lr, float beta1,
+                           float beta2, float eps, float weight_decay, void *stream) {
   if (int e = check_hyper(c, lr, beta1, beta2, eps, weight_decay)) return e;
   if (c->quiesced) return fail(c, RECOVER_ERR_STATE, "adamw_step: a failure is being handled (restore first)");
   const int want = c->adaptive ? finished_by_contributors(c) : c->B;
@@ -793,8 +792,17 @@ int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float
                   c->red_total[b], want);
   }
   if (int e = order_after_previous(c, (hipStream_t)stream, "adamw_step")) return e;
+  if (clear_state) {  // the step count restarts, on the device and on the host alike
+    if (device_state && !c->host_only) {
+      hipError_t he = recover::launch_clear_step_state(device_state, (hipStream_t)stream);
+      if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "adamw_step: %s", hipGetErrorString(he));
+    }
+    c->beta1_pow = c->beta2_pow = 1.0;
+    c->step = 0;
+  }
   StepConsts k;
-  if (int e = prepare_step(c, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "adamw_step")) return e;
+  if (int e = prepare_step(c, device_state, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "adamw_step"))
+    return e;
   if (!c->host_only) {
     hipError_t he = recover::launch_adamw(c->param, c->exp_avg, c->exp_avg_sq, c->grad_out, c->param_bf16, (size_t)c->N,
                                           k.args, k.device_args, (hipStream_t)stream);
@@ -802,6 +810,12 @@ int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float
   }
   commit_iteration(c, k);
   return RECOVER_OK;
+}
+
+int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
+                       void *stream) {
+  if (!c) return RECOVER_ERR_ARG;
+  return adamw_step_impl(c, c->step_state, false, lr, beta1, beta2, eps, weight_decay, stream);
 }
 
 int recover_reduce_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
@@ -819,7 +833,8 @@ int recover_reduce_adamw_step(recover_ctx *c, float lr, float beta1, float beta2
                   microbatches_in(c, b), want);
   if (int e = order_after_previous(c, (hipStream_t)stream, "reduce_adamw_step")) return e;
   StepConsts k;
-  if (int e = prepare_step(c, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "reduce_adamw_step")) return e;
+  if (int e = prepare_step(c, c->step_state, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "reduce_adamw_step"))
+    return e;
   for (const ReduceGroup &g : groups) {
     if (!c->host_only) {
       hipError_t he = recover::launch_reduce_adamw(g.a, c->param, c->exp_avg, c->exp_avg_sq, c->param_bf16,
@@ -852,6 +867,7 @@ int recover_compare(const float *x, const float *ref, int64_t n, recover_compare
   static_assert(sizeof(recover_compare_result) == sizeof(recover::CompareResult), "result layouts must agree");
   if (!x || !ref || !out_device || n < 0) return fail(nullptr, RECOVER_ERR_ARG, "compare: bad argument");
   if ((reinterpret_cast<uintptr_t>(out_device) & 7u) != 0) return fail(nullptr, RECOVER_ERR_ALIGN, "compare: result not 8-byte aligned");
+  if (!aligned16(x) || !aligned16(ref)) return fail(nullptr, RECOVER_ERR_ALIGN, "compare: buffer not 16-byte aligned");
   hipError_t he = recover::launch_compare(x, ref, (size_t)n, reinterpret_cast<recover::CompareResult *>(out_device),
                                           (hipStream_t)stream);
   if (he != hipSuccess) return fail(nullptr, RECOVER_ERR_HIP, "compare: %s", hipGetErrorString(he));
@@ -870,6 +886,12 @@ int recover_set_tuning(int key, int value) {
     t.shape[key - RECOVER_TUNE_WAVES].waves = value;
     return RECOVER_OK;
   }
+  if (key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE || key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE_ADAMW) {
+    const int top = key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE ? 2 : 4;
+    if (value < 1 || value > top) return RECOVER_ERR_ARG;
+    t.shape[key - RECOVER_TUNE_DEPTH].depth = value;
+    return RECOVER_OK;
+  }
   switch (key) {
     case RECOVER_TUNE_THREADS:
       if (value != 64 && value != 256) return RECOVER_ERR_ARG;
@@ -878,14 +900,6 @@ int recover_set_tuning(int key, int value) {
     case RECOVER_TUNE_NONTEMPORAL:
       if (value != 0 && value != 1) return RECOVER_ERR_ARG;
       t.nontemporal = value;
-      return RECOVER_OK;
-    case RECOVER_TUNE_GRID_CAP:
-      if (value < 0 || value > (1 << 24)) return RECOVER_ERR_ARG;
-      t.grid_cap = value;
-      return RECOVER_OK;
-    case RECOVER_TUNE_XCD_CHUNKED:
-      if (value != 0 && value != 1) return RECOVER_ERR_ARG;
-      t.xcd_chunked = value;
       return RECOVER_OK;
   }
   return RECOVER_ERR_ARG;
@@ -902,11 +916,13 @@ int recover_get_tuning(int key, int *value) {
     *value = t.shape[key - RECOVER_TUNE_WAVES].waves;
     return RECOVER_OK;
   }
+  if (key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE || key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE_ADAMW) {
+    *value = t.shape[key - RECOVER_TUNE_DEPTH].depth;
+    return RECOVER_OK;
+  }
   switch (key) {
     case RECOVER_TUNE_THREADS: *value = t.threads; return RECOVER_OK;
     case RECOVER_TUNE_NONTEMPORAL: *value = t.nontemporal; return RECOVER_OK;
-    case RECOVER_TUNE_GRID_CAP: *value = t.grid_cap; return RECOVER_OK;
-    case RECOVER_TUNE_XCD_CHUNKED: *value = t.xcd_chunked; return RECOVER_OK;
   }
   return RECOVER_ERR_ARG;
 }

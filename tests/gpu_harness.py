@@ -70,9 +70,10 @@ def sampled_grad_source(cfg, idx):
     return grad_of
 
 
-def sample_indices(off, n_random, seed, edge=64):
-    """Per tensor: its first and last `edge` elements plus a share of n_random random ones.
-    Returns (sorted unique global indices, offsets of the sampled shard)."""
+def sample_indices(off, n_random, seed, edge=64, windows=()):
+    """Per tensor: its first and last `edge` elements, a share of n_random random ones, and the part of
+    every contiguous window (start, length) that falls inside it.  Returns (sorted unique global indices,
+    offsets of the sampled shard)."""
     rng = np.random.default_rng(seed)
     N = off[-1]
     idx, soff = [], [0]
@@ -83,11 +84,29 @@ def sample_indices(off, n_random, seed, edge=64):
             pick = np.arange(lo, hi)
         else:
             k = max(8, int(n_random * n / max(N, 1)))
-            pick = np.unique(np.concatenate([np.arange(lo, lo + edge), np.arange(hi - edge, hi),
-                                             rng.integers(lo, hi, k)]))
+            parts = [np.arange(lo, lo + edge), np.arange(hi - edge, hi), rng.integers(lo, hi, k)]
+            for w0, wn in windows:
+                a, z = max(lo, w0), min(hi, w0 + wn)
+                if a < z:
+                    parts.append(np.arange(a, z))
+            pick = np.unique(np.concatenate(parts))
         idx.append(pick)
         soff.append(soff[-1] + len(pick))
     return np.concatenate(idx).astype(np.int64), soff
+
+
+def contiguous_windows(N, n_windows, length, seed):
+    """Windows of `length` consecutive elements: across the element whose fp32 byte offset is 2^32 and the one
+    at 2^31 (where 32-bit byte offsets would wrap), at both ends of the shard, and at random odd starts, so
+    that whole workgroup tiles, their borders and tensor borders are compared, not isolated elements."""
+    rng = np.random.default_rng(seed)
+    starts = [0, max(0, N - length)]
+    for e in (1 << 30, 1 << 29):
+        if e + length // 2 < N:
+            starts.append(e - length // 2)
+    while len(starts) < n_windows:
+        starts.append(int(rng.integers(0, max(1, N - length))) | 1)
+    return [(s0, length) for s0 in starts[:n_windows]]
 
 
 def gather(t, idx_dev):
@@ -101,6 +120,35 @@ def max_rel(x, ref):
     ref = np.asarray(ref, np.float64)
     den = np.max(np.abs(ref))
     return float(np.max(np.abs(x - ref)) / den) if den > 0 else float(np.max(np.abs(x - ref)))
+
+
+def assert_adamw_elementwise(before, g, t, hp, got, ref):
+    """Every element of the AdamW state against the fp64 step `ref` = (p, m, v) computed from the same fp32
+    inputs `before` = (p, m, v) and gradient g, with bounds that follow the kernel's roundings (u = 2^-23):
+      exp_avg     product, fused multiply-add, rounded constant 1 - beta1: <= 1.5 u of the terms' size
+                  |beta1 m| + |(1 - beta1) g|; gate 2 u of it (the result itself may cancel)
+      exp_avg_sq  g g, its product with the rounded 1 - beta2, fused multiply-add: <= 2 u v; gate 3 u v
+      param       p (1 - lr wd) and the final fused multiply-add: <= 1.5 u |p|; the update inherits exp_avg's
+                  error and adds sqrt, two rounded constants, a fused multiply-add and the divide: <= 4.5 u of
+                  the update's size; gate 2 u |p| + 8 u |step_size| (|beta1 m| + |(1 - beta1) g|) / denominator.
+    A per-element defect on a small-magnitude entry, invisible to a max-norm bar, fails these."""
+    u = 2.0 ** -23
+    tiny = 1e-44
+    p0, m0, _ = [np.asarray(x, np.float64) for x in before]
+    g = np.asarray(g, np.float64)
+    p, m, v = [np.asarray(x, np.float64) for x in ref]
+    gp, gm, gv = [np.asarray(x, np.float64) for x in got]
+    b1, b2 = hp["beta1"], hp["beta2"]
+    scale_m = np.abs(b1 * m0) + np.abs((1.0 - b1) * g)
+    bad = np.abs(gm - m) > 2 * u * scale_m + tiny
+    assert not bad.any(), "exp_avg: %d elements off, worst %g" % (bad.sum(), np.max(np.abs(gm - m) / (scale_m + tiny)))
+    bad = np.abs(gv - v) > 3 * u * v + tiny
+    assert not bad.any(), "exp_avg_sq: %d elements off" % bad.sum()
+    denom = np.sqrt(v / (1.0 - b2 ** t)) + hp["eps"]
+    upd = hp["lr"] / (1.0 - b1 ** t) * scale_m / denom
+    bound = u * (2 * np.abs(p0) + 8 * upd) + tiny
+    bad = np.abs(gp - p) > bound
+    assert not bad.any(), "param: %d elements off, worst %g of its bound" % (bad.sum(), np.max(np.abs(gp - p) / bound))
 
 
 def bits_equal(a, b):

@@ -15,7 +15,7 @@ from paper_2605_11215_amd.synth import reference_np as S
 from tests.configs import CONFIGS, schedule_of
 from tests.driver import run_iteration, view_oracle, HP
 from tests.gpu_harness import (HipEngine, view_hip, max_rel, bits_equal, sample_indices, gather,
-                               device_grad_source, sampled_grad_source)
+                               device_grad_source, sampled_grad_source, contiguous_windows, assert_adamw_elementwise)
 
 pytestmark = pytest.mark.gpu
 
@@ -31,7 +31,10 @@ def test_config_matches_oracle_on_sampled_elements(cid):
     W, G, off = c["W"], c["G"], c["off"]
     N, T = off[-1], len(off) - 1
     sched = schedule_of(c)
-    idx, soff = sample_indices(off, (1 << 14) if cid == 4 else (1 << 15), seed=cid)
+    # isolated elements, tensor edges, and (on the two large shards) contiguous windows that span whole
+    # workgroup tiles, tensor borders and the elements at byte offsets 2^31 and 2^32
+    windows = contiguous_windows(N, 24, 1 << 14, seed=cid) if cid in (3, 5) else contiguous_windows(N, 8, 1 << 12, seed=cid)
+    idx, soff = sample_indices(off, (1 << 14) if cid == 4 else (1 << 15), seed=cid, windows=windows)
     idx_dev = torch.from_numpy(idx).cuda()
     p0 = S.values(idx, c["seed"], S.TAG_PARAM, 0, 0, 0.02)
     o32 = Proto(W, G, soff, dtype=np.float32)
@@ -68,6 +71,8 @@ def test_config_matches_oracle_on_sampled_elements(cid):
         assert bits_equal(g_gpu, o32.grad_out), "iteration %d: gradient differs from the fp32 oracle" % t
         assert max_rel(g_gpu, o64.grad_out) <= 1e-6
         p, m, v = oracle_adamw.adamw_step(before[0], before[1], before[2], g_gpu, o32.t, **hp32())
+        assert_adamw_elementwise(before, g_gpu, o32.t, hp32(), [gather(x, idx_dev) for x in (s.param, s.exp_avg, s.exp_avg_sq)],
+                                 (p, m, v))
         for got, want in ((s.param, p), (s.exp_avg, m), (s.exp_avg_sq, v)):
             assert max_rel(gather(got, idx_dev), want) <= 1e-6
         for got, want in ((s.param, o32.param), (s.exp_avg, o32.m), (s.exp_avg_sq, o32.v)):

@@ -15,7 +15,7 @@ from paper_2605_11215_amd import binding as B
 from paper_2605_11215_amd import synth
 from paper_2605_11215_amd.synth import reference_np as S
 from tests.driver import run_iteration, view_oracle, HP
-from tests.gpu_harness import HipEngine, view_hip, max_rel, bits_equal
+from tests.gpu_harness import HipEngine, view_hip, max_rel, bits_equal, assert_adamw_elementwise
 
 pytestmark = pytest.mark.gpu
 
@@ -76,6 +76,8 @@ def compare_iteration(o32, s, N, before):
     g_gpu = s.grad_out[:N].cpu().numpy()
     assert bits_equal(g_gpu, o32.grad_out), "iteration gradient differs from the fp32 oracle"
     p, m, v = oracle_adamw.adamw_step(before[0], before[1], before[2], g_gpu, o32.t, **hp32())
+    assert_adamw_elementwise(before, g_gpu, o32.t, hp32(), [x[:N].cpu().numpy() for x in (s.param, s.exp_avg, s.exp_avg_sq)],
+                             (p, m, v))
     assert max_rel(s.param[:N].cpu().numpy(), p) <= 1e-6
     assert max_rel(s.exp_avg[:N].cpu().numpy(), m) <= 1e-6
     assert max_rel(s.exp_avg_sq[:N].cpu().numpy(), v) <= 1e-6
@@ -206,22 +208,22 @@ def test_negative_zero_and_stale_buffers():
 
 
 def test_launch_shapes_do_not_change_the_bits():
-    """Vectors per lane, resident wavefronts per CU, lanes per workgroup, cache hints, grid cap and tile
-    order of every kernel class: the results are the same bits under all of them, through the separate
-    and through the one-pass calls."""
+    """Vectors per lane, resident wavefronts per CU, lanes per workgroup, cache hints and the contributor walk
+    of every kernel class: the results are the same bits under all of them, through the separate and through
+    the one-pass calls."""
     torch = torch_()
     N = OFF[-1]
     g = grads_np(11, N, 1e-3, False)
     ref = None
-    keys = [B.TUNE_NONTEMPORAL, B.TUNE_GRID_CAP, B.TUNE_XCD_CHUNKED, B.TUNE_THREADS] + \
+    keys = [B.TUNE_NONTEMPORAL, B.TUNE_THREADS, B.TUNE_DEPTH + B.KERNEL_REDUCE, B.TUNE_DEPTH + B.KERNEL_REDUCE_ADAMW] + \
            [B.TUNE_VECS + k for k in range(B.KERNEL_CLASSES)] + [B.TUNE_WAVES + k for k in range(B.KERNEL_CLASSES)]
     defaults = {k: B.recover_get_tuning(k) for k in keys}
     assert all(code == 0 for code, _ in defaults.values())
     try:
         for U, waves in ((1, 0), (2, 8), (4, 2), (1, 32), (2, 13)):
-            for nt, cap, xcd, T in ((1, 0, 1, 64), (0, 0, 0, 256), (1, 3, 0, 64), (0, 2, 1, 256)):
-                for key, val in ((B.TUNE_NONTEMPORAL, nt), (B.TUNE_GRID_CAP, cap), (B.TUNE_XCD_CHUNKED, xcd),
-                                 (B.TUNE_THREADS, T)):
+            for nt, depth, T in ((1, 1, 64), (0, 2, 256), (1, 2, 64), (0, 1, 256)):
+                for key, val in ((B.TUNE_NONTEMPORAL, nt), (B.TUNE_THREADS, T), (B.TUNE_DEPTH + B.KERNEL_REDUCE, depth),
+                                 (B.TUNE_DEPTH + B.KERNEL_REDUCE_ADAMW, depth)):
                     assert B.recover_set_tuning(key, val) == 0
                 for k in range(B.KERNEL_CLASSES):
                     assert B.recover_set_tuning(B.TUNE_VECS + k, U) == 0
@@ -234,7 +236,7 @@ def test_launch_shapes_do_not_change_the_bits():
                     if ref is None:
                         ref = cur
                     for x, y in zip(ref, cur):
-                        assert torch.equal(x, y), (U, waves, nt, cap, xcd, T, fuse)
+                        assert torch.equal(x, y), (U, waves, nt, depth, T, fuse)
     finally:
         for k, (_, v) in defaults.items():
             assert B.recover_set_tuning(k, v) == 0
@@ -391,6 +393,21 @@ def test_degenerate_shapes_and_special_values():
         ok = ~np.isnan(got)
         assert bits_equal(got[ok], o.grad_out[ok]), (W, G, got, o.grad_out)
         assert got[3] != 0 and got[4] != 0                      # subnormals are kept, not flushed
+    # the bf16 copy of the parameters keeps a NaN a NaN whatever its payload (the rounding increment would
+    # otherwise carry 0x7F800001 into Inf and 0x7FFFFFFF / 0xFFFFFFFF into zero)
+    bits = np.array([0x7F800001, 0x7FFFFFFF, 0xFFFFFFFF, 0x7FC00000, 0x7F7FFFFF, 0x3F80FFFF, 0x7F800000, 0xFF800000],
+                    np.uint32)
+    s = B.Shard(1, 1, [0, len(bits)], param_bf16=True)
+    s.param[:len(bits)].copy_(torch.from_numpy(bits.view(np.float32)))
+    s.accumulate(0, 0, torch.zeros(8, device="cuda"))
+    s.reduce()
+    s.adamw_step(lr=0.0, beta1=0.0, beta2=0.0, eps=1.0, weight_decay=0.0)      # leaves finite parameters unchanged
+    pb = s.param_bf16[:len(bits)].view(torch.int16).cpu().numpy().view(np.uint16)
+    pf = s.param[:len(bits)].cpu().numpy()
+    assert np.array_equal(pb, S.f32_to_bf16_bits(pf))
+    back = S.bf16_bits_to_f32(pb)
+    assert np.all(np.isnan(back[:4])) and np.isinf(back[4]) and back[5] == np.float32(1.0078125)
+    assert back[6] == np.inf and back[7] == -np.inf
 
 
 @pytest.mark.parametrize("random_streams", [False, True])
@@ -503,6 +520,8 @@ def test_device_compare_matches_numpy():
             y[7] = np.nan
             x[9] = -0.0
             y[9] = 0.0                                            # equal as numbers, different bits
+            x[11] = y[11] = np.inf                                # equal infinities differ by nothing
+            x[12] = y[12] = -np.inf
         got = B.compare_tensors(torch.from_numpy(np.append(x, 0).astype(np.float32)).cuda(),
                                 torch.from_numpy(np.append(y, 0).astype(np.float32)).cuda(), n)
         xb, yb = x.view(np.uint32).astype(np.uint64), y.view(np.uint32).astype(np.uint64)
@@ -512,8 +531,15 @@ def test_device_compare_matches_numpy():
         assert got["checksum_x"] == int(np.sum(xb * w, dtype=np.uint64))
         assert got["checksum_ref"] == int(np.sum(yb * w, dtype=np.uint64))
         ok = ~(np.isnan(x) | np.isnan(y))
-        assert got["max_abs_diff"] == (np.max(np.abs(x[ok] - y[ok])) if ok.any() else 0.0)
+        with np.errstate(invalid="ignore"):
+            d = np.where(xb == yb, np.float32(0), np.abs(x - y))
+        assert got["max_abs_diff"] == (np.max(d[ok]) if ok.any() else 0.0)
         assert got["max_abs_ref"] == (np.max(np.abs(y[ok])) if ok.any() else 0.0)
+    # opposite infinities are infinitely far apart, and a NaN payload survives the bf16 rounding of the parameters
+    a = torch.tensor([np.inf, 1.0, 2.0, 3.0, 4.0], device="cuda")
+    b = torch.tensor([-np.inf, 1.0, 2.0, 3.0, 4.0], device="cuda")
+    got = B.compare_tensors(a, b, 5)
+    assert got["max_abs_diff"] == np.inf and got["n_mismatch"] == 1 and got["n_nan"] == 0
 
 
 def test_device_step_state_gives_the_same_bits_as_host_constants():
