@@ -206,6 +206,20 @@ int recover_reduce(recover_ctx *ctx, int tensor_begin, int tensor_end, uint32_t 
 int recover_adamw_step(recover_ctx *ctx, float lr, float beta1, float beta2, float eps, float weight_decay,
                        void *hip_stream);
 
+/* recover_adamw_step for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc) and still want the step count to live on the device:
+ * the 64-byte step state that recover_config.step_state otherwise brings in is slot `slot` of an array of
+ * RECOVER_STATIC_STEP_SLOTS states that the library keeps in a file-scope device array (4 KiB on every GPU
+ * the library runs on, held until the process ends; the slot of the CURRENT device is used).  restart != 0:
+ * the slot is cleared first (by a kernel, not a memset), so this is step 1; otherwise the slot's count goes on
+ * from the last call that used it, whichever context made it: a slot belongs to one context at a time, the
+ * caller assigns the slots, and calls that use one slot from several streams or threads at once race.
+ * Allocates nothing.  ERR_ARG: slot outside [0, RECOVER_STATIC_STEP_SLOTS).  ERR_STATE: the context has a
+ * caller-owned step state; otherwise as recover_adamw_step, with the same bits in param, exp_avg, exp_avg_sq. */
+#define RECOVER_STATIC_STEP_SLOTS 64
+int recover_adamw_step_static(recover_ctx *ctx, int slot, int restart, float lr, float beta1, float beta2, float eps,
+                              float weight_decay, void *hip_stream);
+
 /* recover_reduce over all tensors (not in place) followed by recover_adamw_step, in ONE pass over the
  * contributors' buffers and the optimiser state: 4 R_c + 24 bytes per element instead of 4 R_c + 32.  grad_out
  * is written only with RECOVER_FUSED_WRITE_GRAD.  Same checks (Eq. 1), same bits in param, exp_avg, exp_avg_sq

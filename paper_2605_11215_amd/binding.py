@@ -20,6 +20,7 @@ RESTORE_SKIP, RESTORE_BLOCKING, RESTORE_NONBLOCKING = 0, 1, 2
 FLAG_ADAPTIVE, FLAG_ANY_ORDER, FLAG_HOST_ONLY = 1, 2, 4
 REDUCE_INPLACE = 1
 MAX_REPLICAS = 64
+STATIC_STEP_SLOTS = 64
 
 FUSED_WRITE_GRAD = 1
 (KERNEL_ACCUMULATE_FIRST_F32, KERNEL_ACCUMULATE_RMW_F32, KERNEL_ACCUMULATE_FIRST_BF16, KERNEL_ACCUMULATE_RMW_BF16,
@@ -31,7 +32,7 @@ EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_acc
            "recover_reduce_adamw_step", "recover_snapshot", "recover_restore",
            "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
            "recover_committed_ids", "recover_compare", "recover_last_error", "recover_set_tuning",
-           "recover_get_tuning"]
+           "recover_get_tuning", "recover_adamw_step_static"]
 
 
 class RecoverError(RuntimeError):
@@ -82,6 +83,7 @@ def lib():
         L.recover_policy_adjust.argtypes = [P, C.POINTER(C.c_int32), I, C.POINTER(Decision)]
         L.recover_reduce.argtypes = [P, I, I, U32, VP]
         L.recover_adamw_step.argtypes = [P, F, F, F, F, F, VP]
+        L.recover_adamw_step_static.argtypes = [P, I, I, F, F, F, F, F, VP]
         L.recover_query.argtypes = [P, C.POINTER(Decision)]
         L.recover_committed_ids.argtypes = [P, I, C.POINTER(U32), I]
         L.recover_compare.argtypes = [VP, VP, C.c_int64, VP, VP]
@@ -197,6 +199,10 @@ def recover_reduce(ctx, tensor_begin, tensor_end, flags=0, stream=0):
 
 def recover_adamw_step(ctx, lr, beta1, beta2, eps, weight_decay, stream=0):
     return lib().recover_adamw_step(ctx, lr, beta1, beta2, eps, weight_decay, stream or None)
+
+
+def recover_adamw_step_static(ctx, slot, restart, lr, beta1, beta2, eps, weight_decay, stream=0):
+    return lib().recover_adamw_step_static(ctx, slot, int(restart), lr, beta1, beta2, eps, weight_decay, stream or None)
 
 
 def recover_query(ctx, W_init):

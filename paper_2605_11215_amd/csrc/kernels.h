@@ -115,6 +115,11 @@ struct StepState {
 };
 static_assert(sizeof(StepState) == 64, "StepState is 64 bytes");
 
+// Step states owned by the library, for callers that cannot allocate device memory: kStaticStepSlots
+// slots of one StepState each in a file-scope device array (every GPU holds its own copy).  Gives the
+// address of slot `slot` on the CURRENT device; the symbol is resolved once per device.
+constexpr int kStaticStepSlots = 64;
+hipError_t static_step_state(int slot, StepState **out);
 // Zero-fills *st with a one-thread kernel (no memset node, so the call can be captured into a graph).
 hipError_t launch_clear_step_state(StepState *st, hipStream_t s);
 

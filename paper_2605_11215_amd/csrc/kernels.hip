@@ -790,6 +790,29 @@ hipError_t launch_reduce(const ReduceArgs &a, size_t begin, size_t end, hipStrea
   return hipGetLastError();
 }
 
+// Library-owned step states (4 KiB per GPU, held until the process ends).  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels get the resolved device address as an argument.
+static __device__ __align__(256) StepState scratch[kStaticStepSlots];
+
+hipError_t static_step_state(int slot, StepState **out) {
+  constexpr int kMaxDevices = 64;
+  static StepState *base[kMaxDevices] = {};
+  if (slot < 0 || slot >= kStaticStepSlots) return hipErrorInvalidValue;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!base[dev]) {
+    StepState *p = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    base[dev] = p;
+  }
+  *out = base[dev] + slot;
+  return hipSuccess;
+}
+
 __global__ void k_clear_step_state(StepState *st) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     st->step = 0;

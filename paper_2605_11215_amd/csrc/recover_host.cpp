@@ -15,6 +15,7 @@
 #include "kernels.h"
 
 using recover::kMaxReplicas;
+static_assert(RECOVER_STATIC_STEP_SLOTS == recover::kStaticStepSlots, "slot counts of the header and of the kernels must agree");
 static_assert(RECOVER_KERNEL_CLASSES == recover::kNumClasses, "kernel classes of the header and of the launchers must agree");
 
 struct recover_ctx {
@@ -816,6 +817,22 @@ int recover_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float
                        void *stream) {
   if (!c) return RECOVER_ERR_ARG;
   return adamw_step_impl(c, c->step_state, false, lr, beta1, beta2, eps, weight_decay, stream);
+}
+
+int recover_adamw_step_static(recover_ctx *c, int slot, int restart, float lr, float beta1, float beta2, float eps,
+                              float weight_decay, void *stream) {
+  if (!c) return RECOVER_ERR_ARG;
+  if (slot < 0 || slot >= RECOVER_STATIC_STEP_SLOTS)
+    return fail(c, RECOVER_ERR_ARG, "adamw_step_static: slot %d outside [0, %d): the library holds %d step states per GPU",
+                slot, RECOVER_STATIC_STEP_SLOTS, RECOVER_STATIC_STEP_SLOTS);
+  if (c->step_state)
+    return fail(c, RECOVER_ERR_STATE, "adamw_step_static: the context already has a caller-owned step state");
+  recover::StepState *st = nullptr;
+  if (!c->host_only) {
+    hipError_t he = recover::static_step_state(slot, &st);
+    if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "adamw_step_static: %s", hipGetErrorString(he));
+  }
+  return adamw_step_impl(c, st, restart != 0, lr, beta1, beta2, eps, weight_decay, stream);
 }
 
 int recover_reduce_adamw_step(recover_ctx *c, float lr, float beta1, float beta2, float eps, float weight_decay,
