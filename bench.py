@@ -33,7 +33,7 @@ POOL = 4
 # Arithmetic type of the path: accumulators, contributor sum, the division and AdamW are all fp32 (bf16 is
 # only the storage type of the incoming microbatch gradients of configs[2] and configs[4]).
 ARITHMETIC = "f32"
-SLAB = {"on": True, "pad": 4 << 20}          # buffer placement, see binding.alloc_slab
+SLAB = {"on": True, "pad": 4 << 20, "contiguous": True}          # buffer placement, see binding.alloc_slab
 
 WORKLOAD_TEXT = {
     1: "configs[0] tiny: 1,048,576 fp32 elements, R=4, M=8 (cache- and launch-bound, not an HBM measurement)",
@@ -119,7 +119,7 @@ class Leg:
         self.N, self.M, self.T = self.off[-1], c["W"] * c["G"], len(self.off) - 1
         gdt, self.gcode = (torch.bfloat16, B.BF16) if c["bf16"] else (torch.float32, B.F32)
         self.sh = B.Shard(self.W, self.G, self.off, device="cuda:0", snapshots=True, slab=SLAB["on"],
-                          slab_pad=SLAB["pad"], extra=[(gdt, self.N)] * POOL)
+                          slab_pad=SLAB["pad"], extra=[(gdt, self.N)] * POOL, contiguous=SLAB["contiguous"])
         synth.fill_device(self.sh.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=self.N)
         self.pool = [synth.fill_device(g, c["seed"], S.TAG_GRAD, j, 0, c["scale"], c["kind"])
                      for j, g in enumerate(self.sh.extra)]
@@ -305,9 +305,11 @@ class Leg:
         med = lambda v: sorted(v)[len(v) // 2]
         out["snapshot_all_replicas"] = dict(ms=med(snap_t), GBps=8 * W * N / med(snap_t) / 1e6, launches=1)
         out["restore_all_replicas"] = dict(ms=med(rest_t), GBps=8 * W * N / med(rest_t) / 1e6, launches=1)
-        out["ceilings"] = dict(copy_GBps=8 * W * N / min(snap_t) / 1e6, read_only_GBps=8 * N / min(cmp_t) / 1e6,
-                               what="best of 5: copy = recover_snapshot of all replicas (k_copy_many); read-only = "
-                                    "recover_compare over two buffers (k_compare)")
+        out["ceilings"] = dict(copy_GBps=8 * W * N / min(snap_t) / 1e6, compare_two_reads_GBps=8 * N / min(cmp_t) / 1e6,
+                               what="best of 5 with the library's own kernels on this workload's buffers: copy = "
+                                    "recover_snapshot of all replicas (k_copy_many, 1 read : 1 write); compare = "
+                                    "recover_compare over two buffers (k_compare: two reads, no write; a verification "
+                                    "kernel with 64-bit checksum arithmetic per element, not a tuned read probe)")
 
         # Non-blocking restoration (Alg. 5): rewind every replica from its snapshot while the main stream
         # generates the next microbatch's gradient (the stand-in for the extended pass's forward/backward),
@@ -414,9 +416,17 @@ def main():
     ap.add_argument("--per-config", default="2,3,4",
                     help="comma list of further workloads timed after the headline ('' = none)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed region (for profiling runs)")
+    ap.add_argument("--fused-steps", type=int, default=0,
+                    help="with --no-extras: also run this many iterations through the one-pass reduce+AdamW call "
+                         "(so that a counter run sees that kernel)")
     ap.add_argument("--separate-allocations", action="store_true",
                     help="one device allocation per buffer instead of one slab per context (placement A/B)")
     ap.add_argument("--slab-pad-kib", type=int, default=4096, help="padding between the buffers of a slab")
+    ap.add_argument("--no-contiguous", action="store_true",
+                    help="ordinary allocation for the slab instead of asking for physically contiguous memory first")
+    ap.add_argument("--realloc", type=int, default=0,
+                    help="placement study instead of the benchmark: allocate, time and free the workload's buffers "
+                         "this many times in ONE process and print every allocation's kernel rates")
     ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -430,12 +440,29 @@ def main():
         print("bench.py: no GPU visible; this library has no CPU path", file=sys.stderr)
         sys.exit(3)
     B.lib()
-    SLAB["on"], SLAB["pad"] = not a.separate_allocations, a.slab_pad_kib << 10
+    SLAB["on"], SLAB["pad"], SLAB["contiguous"] = not a.separate_allocations, a.slab_pad_kib << 10, not a.no_contiguous
     for kv in filter(None, a.tuning.split(",")):
         k, v = kv.split("=")
         assert B.recover_set_tuning(int(k), int(v)) == 0, kv
     torch.cuda.set_device(0)
 
+    if a.realloc > 0:
+        # Same process, same code, same virtual layout (the slab lands at the same address): what changes from one
+        # allocation to the next is the physical memory behind it.  A 1 GiB allocation is kept after every second
+        # round so that the driver cannot hand the same frames back.
+        rows, keep = [], []
+        for i in range(a.realloc):
+            lk = Leg(a.workload)
+            r = lk.measure(a.steps, a.warmup, min(a.settle_seconds, 3.0))
+            dtf = lk.timed(max(2, a.steps // 4), fused=True)
+            rows.append(dict(allocation=i, slab_address=hex(lk.sh._slab.data_ptr()) if SLAB["on"] else None,
+                             contiguous=getattr(lk.sh, "contiguous", False),
+                             GBps=r["value"], kernel_GBps=r["kernel_GBps"], fused_iteration_ms=dtf * 1e3))
+            lk.close()
+            if i % 2 == 0:
+                keep.append(torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0"))
+        print(json.dumps({"placement_study": WORKLOAD_TEXT[a.workload], "slab": SLAB["on"], "allocations": rows}))
+        return
     leg = Leg(a.workload)
     head = leg.measure(a.steps, a.warmup, a.settle_seconds)
     out = {
@@ -450,6 +477,9 @@ def main():
     }
     for k in ("settle", "microbatches_per_s", "iteration_ms_events", "kernel_GBps", "phase_ms"):
         out[k] = head[k]
+    if a.no_extras and a.fused_steps > 0:
+        dtf = leg.timed(a.fused_steps, fused=True)
+        out["fused_reduce_adamw"] = dict(ms_per_step=dtf * 1e3)
     if not a.no_extras:
         out.update(leg.extras(head["ms_per_step"], a.steps))
         out["batched_launches"] = leg.batched(a.steps) if a.workload == 1 else None

@@ -249,6 +249,15 @@ typedef struct {
 } recover_compare_result;
 int recover_compare(const float *x, const float *ref, int64_t n, recover_compare_result *out_device, void *hip_stream);
 
+/* Allocation helpers for callers that want the buffers of a context in ONE device allocation with a fixed relative
+ * placement (the context calls themselves never allocate).  recover_device_alloc gives `bytes` of device memory on
+ * the current device, 2 MiB-aligned; contiguous != 0 asks the driver for physically contiguous memory
+ * (hipDeviceMallocContiguous), which keeps the translation fragments large, and fails with ERR_HIP if the driver cannot
+ * provide it (the caller then allocates normally).  The memory is not cleared.  recover_device_free releases it; the
+ * caller makes sure no work that uses it is in flight. */
+int recover_device_alloc(uint64_t bytes, int contiguous, void **out_device);
+int recover_device_free(void *device);
+
 /* Message of the last negative return on this context (or of recover_init if ctx == NULL). */
 const char *recover_last_error(const recover_ctx *ctx);
 
@@ -271,8 +280,7 @@ enum { /* keys of recover_set_tuning / recover_get_tuning */
   RECOVER_TUNE_THREADS = 7,     /* {64, 256}: lanes per workgroup */
   RECOVER_TUNE_VECS = 16,       /* + kernel class: 128-bit vectors per lane per stream {1, 2, 4} */
   RECOVER_TUNE_WAVES = 32,      /* + kernel class: wavefronts resident per CU, 0 = hardware limit, else 2..32 */
-  RECOVER_TUNE_DEPTH = 48       /* + RECOVER_KERNEL_REDUCE or _REDUCE_ADAMW: contributors a wavefront loads at a time {1, 2};
-                                   _REDUCE_ADAMW also {3, 4} = {1, 2} with the optimiser state loaded before the walk */
+  RECOVER_TUNE_DEPTH = 48       /* + RECOVER_KERNEL_REDUCE or _REDUCE_ADAMW: contributors a wavefront loads at a time {1, 2} */
 };
 int recover_set_tuning(int key, int value);
 int recover_get_tuning(int key, int *value);

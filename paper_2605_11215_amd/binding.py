@@ -32,7 +32,7 @@ EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_acc
            "recover_reduce_adamw_step", "recover_snapshot", "recover_restore",
            "recover_policy_adjust", "recover_reduce", "recover_adamw_step", "recover_query",
            "recover_committed_ids", "recover_compare", "recover_last_error", "recover_set_tuning",
-           "recover_get_tuning", "recover_adamw_step_static"]
+           "recover_get_tuning", "recover_adamw_step_static", "recover_device_alloc", "recover_device_free"]
 
 
 class RecoverError(RuntimeError):
@@ -90,6 +90,8 @@ def lib():
         L.recover_last_error.argtypes = [P]
         L.recover_last_error.restype = C.c_char_p
         L.recover_set_tuning.argtypes = [I, I]
+        L.recover_device_alloc.argtypes = [C.c_uint64, I, C.POINTER(VP)]
+        L.recover_device_free.argtypes = [VP]
         L.recover_get_tuning.argtypes = [I, C.POINTER(C.c_int)]
         for name in EXPORTS:
             if name != "recover_last_error":
@@ -252,23 +254,62 @@ def recover_get_tuning(key):
     return code, v.value
 
 
-def alloc_slab(specs, device="cuda:0", pad_bytes=4 << 20, align=2 << 20):
+class DeviceSlab:
+    """Device memory from recover_device_alloc, visible to torch through __cuda_array_interface__."""
+
+    def __init__(self, nbytes, contiguous):
+        p = C.c_void_p()
+        code = lib().recover_device_alloc(nbytes, int(contiguous), C.byref(p))
+        if code < 0:
+            raise RecoverError(code, recover_last_error(None))
+        self.ptr, self.nbytes = p.value, nbytes
+        self.__cuda_array_interface__ = dict(shape=(nbytes,), typestr="|u1", data=(self.ptr, False), version=2, strides=None)
+
+    def data_ptr(self):
+        return self.ptr
+
+    def free(self):
+        if self.ptr:
+            check(lib().recover_device_free(self.ptr))
+            self.ptr = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def alloc_slab(specs, device="cuda:0", pad_bytes=4 << 20, align=2 << 20, contiguous=False):
     """One device allocation carved into zero-filled flat tensors: specs = [(torch dtype, numel), ...].  Every
     tensor starts `align`-aligned inside the slab and is followed by `pad_bytes` of padding.  A single
     allocation gives the buffers of a context fixed relative placement (separate allocations land wherever
-    the driver puts them, and HBM efficiency of the multi-stream kernels then differs from run to run)."""
+    the driver puts them, and HBM efficiency of the multi-stream kernels then differs from run to run).
+    contiguous: ask the driver for physically contiguous memory first (recover_device_alloc) and fall back to an
+    ordinary torch allocation if it cannot provide it.  Returns (owner of the memory, tensors); the owner must
+    outlive the tensors."""
     import torch
     sizes = [n * torch.empty(0, dtype=dt).element_size() for dt, n in specs]
     offs, total = [], 0
     for b in sizes:
         offs.append(total)
         total += (b + align - 1) // align * align + pad_bytes
-    slab = torch.zeros(total + align, dtype=torch.uint8, device=device)
-    base = (-slab.data_ptr()) % align
+    owner, flat = None, None
+    if contiguous and str(device).startswith("cuda"):
+        try:
+            with torch.cuda.device(device):
+                owner = DeviceSlab(total + align, True)
+            flat = torch.as_tensor(owner, device=device)
+            flat.zero_()
+        except RecoverError:
+            owner = None
+    if flat is None:
+        owner = flat = torch.zeros(total + align, dtype=torch.uint8, device=device)
+    base = (-flat.data_ptr()) % align
     out = []
     for (dt, n), o, b in zip(specs, offs, sizes):
-        out.append(slab[base + o: base + o + b].view(dt))
-    return slab, out
+        out.append(flat[base + o: base + o + b].view(dt))
+    return owner, out
 
 
 class Shard:
@@ -279,9 +320,9 @@ class Shard:
     current stream."""
 
     def __init__(self, W_init, G_init, tensor_offsets, device="cuda:0", snapshots=True, flags=0, param_bf16=False,
-                 host_only=False, device_step=False, slab=False, slab_pad=4 << 20, extra=()):
+                 host_only=False, device_step=False, slab=False, slab_pad=4 << 20, extra=(), contiguous=False):
         """slab: all buffers (and the `extra` = [(dtype, numel), ...] tensors, returned in self.extra) are carved
-        from one allocation, see alloc_slab."""
+        from one allocation, see alloc_slab (contiguous: physically contiguous if the driver can)."""
         import torch
         self.torch = torch
         self.W, self.G = W_init, G_init
@@ -298,7 +339,8 @@ class Shard:
             if slab:
                 n_f32 = W_init * (2 if snapshots else 1) + 4
                 specs = [(torch.float32, n)] * n_f32 + ([(torch.bfloat16, n)] if param_bf16 else []) + list(extra)
-                self._slab, bufs = alloc_slab(specs, device, slab_pad)
+                self._slab, bufs = alloc_slab(specs, device, slab_pad, contiguous=contiguous)
+                self.contiguous = isinstance(self._slab, DeviceSlab)
                 z = lambda dt=torch.float32: bufs.pop(0)
             else:
                 z = lambda dt=torch.float32: torch.zeros(n, dtype=dt, device=device)
@@ -321,6 +363,13 @@ class Shard:
         if self.ctx:
             recover_destroy(self.ctx)
             self.ctx = None
+        slab = getattr(self, "_slab", None)
+        if isinstance(slab, DeviceSlab):          # the views go first, then the memory they look at
+            self.torch.cuda.synchronize()
+            self.acc = self.snap = self.extra = None
+            self.grad_out = self.param = self.exp_avg = self.exp_avg_sq = self.param_bf16 = None
+            slab.free()
+        self._slab = None
 
     def __del__(self):
         try:

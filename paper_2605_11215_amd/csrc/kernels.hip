@@ -480,8 +480,7 @@ __global__ __launch_bounds__(64) void k_adamw_ragged(float *__restrict__ p, floa
 // update of k_adamw in one pass; the gradient goes to HBM only if WRITE_GRAD.  4 R_c + 24 (+4) bytes
 // per element.
 // ---------------------------------------------------------------------------------------------
-// EARLY: the loads of p, m, v are issued before the contributor walk instead of after it.
-template <int T, int U, bool NT, bool WRITE_GRAD, bool BF16OUT, int D, bool DEV, bool EARLY>
+template <int T, int U, bool NT, bool WRITE_GRAD, bool BF16OUT, int D, bool DEV>
 __global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, AdamPtrs s, size_t first, size_t nvec, AdamArgs h_arg,
                                                     const AdamArgs *__restrict__ h_dev) {
   const AdamArgs h = DEV ? *h_dev : h_arg;
@@ -494,9 +493,8 @@ __global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, AdamPtrs s, si
     for (int u = 0; u < U; ++u) ok[u] = FULL || base + size_t(T) * u < nvec;
     f32x4 sum[U];
     AdamTile<U> x;
-    if (EARLY) adam_load<T, U, NT>(s, base, ok, x);  // in flight during the walk
     contributor_sum<T, U, NT, D>(a, first, base, ok, sum);
-    if (!EARLY) adam_load<T, U, NT>(s, base, ok, x);
+    adam_load<T, U, NT>(s, base, ok, x);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       sum[u].x = sum[u].x / a.divisor;
@@ -889,23 +887,18 @@ hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v
       constexpr int T = decltype(t)::value, U = decltype(u)::value;
       constexpr bool NT = decltype(nt)::value;
       const unsigned lds = lds_share(sh.waves, T);
-      auto go = [&](auto wg, auto bf, auto d, auto dev, auto early) {
-        hipLaunchKernelGGL((k_reduce_adamw<T, U, NT, decltype(wg)::value, decltype(bf)::value, decltype(d)::value / 10,
-                                           decltype(dev)::value, decltype(early)::value>),
+      auto go = [&](auto wg, auto bf, auto d, auto dev) {
+        hipLaunchKernelGGL((k_reduce_adamw<T, U, NT, decltype(wg)::value, decltype(bf)::value, decltype(d)::value,
+                                           decltype(dev)::value>),
                            dim3(grid), dim3(T), lds, s, a, q, sp.vbegin, sp.nvec, h, device_args);
       };
       auto with_dev = [&](auto wg, auto bf, auto d) {
-        constexpr bool early = decltype(d)::value % 10 != 0;
-        if (device_args) go(wg, bf, d, std::true_type{}, std::integral_constant<bool, early>{});
-        else go(wg, bf, d, std::false_type{}, std::integral_constant<bool, early>{});
+        if (device_args) go(wg, bf, d, std::true_type{});
+        else go(wg, bf, d, std::false_type{});
       };
-      auto with_d = [&](auto wg, auto bf) {  // depth: 1, 2 = contributors in flight; +2 = p, m, v loaded before the walk
-        switch (sh.depth) {
-          case 1: with_dev(wg, bf, Int<10>{}); break;
-          case 3: with_dev(wg, bf, Int<11>{}); break;
-          case 4: with_dev(wg, bf, Int<21>{}); break;
-          default: with_dev(wg, bf, Int<20>{}); break;
-        }
+      auto with_d = [&](auto wg, auto bf) {
+        if (sh.depth == 1) with_dev(wg, bf, Int<1>{});
+        else with_dev(wg, bf, Int<2>{});
       };
       auto with_bf = [&](auto wg) {
         if (p_bf16) with_d(wg, std::true_type{});

@@ -880,6 +880,26 @@ int recover_committed_ids(recover_ctx *c, int r, uint32_t *ids_out, int cap) {
   return n;
 }
 
+int recover_device_alloc(uint64_t bytes, int contiguous, void **out) {
+  if (!out || bytes == 0) return fail(nullptr, RECOVER_ERR_ARG, "device_alloc: bad argument");
+  *out = nullptr;
+  void *p = nullptr;
+  hipError_t he = contiguous ? hipExtMallocWithFlags(&p, (size_t)bytes, hipDeviceMallocContiguous) : hipMalloc(&p, (size_t)bytes);
+  if (he != hipSuccess) {
+    (void)hipGetLastError();  // do not leave the error for the next call
+    return fail(nullptr, RECOVER_ERR_HIP, "device_alloc: %s", hipGetErrorString(he));
+  }
+  *out = p;
+  return RECOVER_OK;
+}
+
+int recover_device_free(void *p) {
+  if (!p) return RECOVER_OK;
+  hipError_t he = hipFree(p);
+  if (he != hipSuccess) return fail(nullptr, RECOVER_ERR_HIP, "device_free: %s", hipGetErrorString(he));
+  return RECOVER_OK;
+}
+
 int recover_compare(const float *x, const float *ref, int64_t n, recover_compare_result *out_device, void *stream) {
   static_assert(sizeof(recover_compare_result) == sizeof(recover::CompareResult), "result layouts must agree");
   if (!x || !ref || !out_device || n < 0) return fail(nullptr, RECOVER_ERR_ARG, "compare: bad argument");
@@ -904,8 +924,7 @@ int recover_set_tuning(int key, int value) {
     return RECOVER_OK;
   }
   if (key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE || key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE_ADAMW) {
-    const int top = key == RECOVER_TUNE_DEPTH + RECOVER_KERNEL_REDUCE ? 2 : 4;
-    if (value < 1 || value > top) return RECOVER_ERR_ARG;
+    if (value != 1 && value != 2) return RECOVER_ERR_ARG;
     t.shape[key - RECOVER_TUNE_DEPTH].depth = value;
     return RECOVER_OK;
   }
