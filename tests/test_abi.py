@@ -385,3 +385,17 @@ def test_context_without_snapshot_buffers_gets_past_a_failure():
     assert B.recover_restore(s.ctx, -1, 1) == B.ERR_NO_SNAPSHOT
     assert B.recover_restore(s.ctx, 3, 1) == B.ERR_STATE   # dead replica
     s.close()
+
+
+def test_slab_layout_on_the_cpu():
+    """alloc_slab's carving (alignment, padding, dtypes, zero fill) with CPU memory; no device call."""
+    import torch
+    owner, bufs = B.alloc_slab([(torch.float32, 1000), (torch.bfloat16, 77), (torch.float32, 5)], device="cpu",
+                               pad_bytes=4096, align=4096)
+    assert [b.dtype for b in bufs] == [torch.float32, torch.bfloat16, torch.float32]
+    assert [b.numel() for b in bufs] == [1000, 77, 5]
+    assert all(b.data_ptr() % 4096 == 0 for b in bufs)
+    assert bufs[1].data_ptr() - bufs[0].data_ptr() == 4096 + 4096 and bufs[2].data_ptr() - bufs[1].data_ptr() == 4096 + 4096
+    assert all(float(b.float().abs().sum()) == 0 for b in bufs)
+    bufs[0].fill_(1.0)
+    assert float(bufs[1].float().abs().sum()) == 0

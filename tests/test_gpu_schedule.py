@@ -137,3 +137,46 @@ def test_context_without_snapshot_buffers_gets_past_a_failure_on_the_gpu():
     assert_adamw_elementwise(before, g_gpu, 1, hp32(), [x[:N].cpu().numpy() for x in (s.param, s.exp_avg, s.exp_avg_sq)], ref)
     assert o.advance()["G_cur"] == s.advance()["G_cur"] == 3
     s.close()
+
+
+def test_slab_placement_gives_the_same_bits_and_frees_its_memory():
+    """All buffers of a context carved from one allocation (physically contiguous if the driver can give it, through
+    recover_device_alloc): same results as separately allocated buffers, every buffer 2 MiB-aligned, and the memory
+    is returned on close."""
+    import torch
+    off = [0, 7, 4099, 70000]
+    N = off[-1]
+    g = [torch.from_numpy(S.fill(N, 3, S.TAG_GRAD, j, 0, 1e-3)).cuda() for j in range(4)]
+    p0 = torch.from_numpy(S.fill(N, 3, S.TAG_PARAM, 0, 0, 0.02)).cuda()
+    free_before = torch.cuda.mem_get_info()[0]
+    shards = [B.Shard(2, 2, off, param_bf16=True),
+              B.Shard(2, 2, off, param_bf16=True, slab=True, extra=[(torch.float32, N)] * 2),
+              B.Shard(2, 2, off, param_bf16=True, slab=True, contiguous=True, extra=[(torch.bfloat16, 5)])]
+    assert shards[2].contiguous in (True, False)                    # the driver may refuse; then it is an ordinary slab
+    for s in shards[1:]:
+        bufs = s.acc + s.snap + [s.grad_out, s.param, s.exp_avg, s.exp_avg_sq, s.param_bf16] + s.extra
+        assert all(b.data_ptr() % (2 << 20) == 0 for b in bufs)
+        ends = sorted((b.data_ptr(), b.data_ptr() + b.numel() * b.element_size()) for b in bufs)
+        assert all(a[1] + (4 << 20) <= b[0] for a, b in zip(ends, ends[1:]))            # padding between neighbours
+        assert all(float(b.float().abs().max()) == 0 for b in bufs)                     # zero-filled
+    for s in shards:
+        s.param[:N].copy_(p0)
+        for k in range(2):
+            for r in range(2):
+                assert s.accumulate(r, r + 2 * k, g[2 * k + r])
+        s.snapshot()
+        s.reduce()
+        s.adamw_step(**hp32())
+    ref = shards[0]
+    for s in shards[1:]:
+        for a, b in ((ref.grad_out, s.grad_out), (ref.param, s.param), (ref.exp_avg, s.exp_avg), (ref.exp_avg_sq, s.exp_avg_sq),
+                     (ref.snap[1], s.snap[1])):
+            assert torch.equal(a[:N].view(torch.int32), b[:N].view(torch.int32))
+        assert torch.equal(ref.param_bf16[:N].view(torch.int16), s.param_bf16[:N].view(torch.int16))
+    for s in shards:
+        s.close()
+    del shards, ref, s, bufs
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    assert torch.cuda.mem_get_info()[0] >= free_before - (64 << 20)
+    assert B.lib().recover_device_free(None) == B.OK
