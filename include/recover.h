@@ -273,7 +273,9 @@ enum { /* kernel classes that have a launch shape of their own */
   RECOVER_KERNEL_REDUCE = 5,
   RECOVER_KERNEL_ADAMW = 6,
   RECOVER_KERNEL_REDUCE_ADAMW = 7,
-  RECOVER_KERNEL_CLASSES = 8
+  RECOVER_KERNEL_ACCUMULATE_SNAPSHOT_F32 = 8,  /* recover_accumulate_snapshot: the dual store */
+  RECOVER_KERNEL_ACCUMULATE_SNAPSHOT_BF16 = 9,
+  RECOVER_KERNEL_CLASSES = 10
 };
 enum { /* keys of recover_set_tuning / recover_get_tuning */
   RECOVER_TUNE_NONTEMPORAL = 1, /* {0, 1}: streaming cache hints on loads and stores */

@@ -19,6 +19,8 @@ enum KernelClass {
   kReduce,
   kAdamw,
   kReduceAdamw,
+  kAccSnapF32,       // accumulate with the second store to the snapshot (first or read-modify-write)
+  kAccSnapBf16,
   kNumClasses
 };
 
@@ -35,7 +37,8 @@ struct Shape {
 struct Tuning {
   int threads = 64;     // lanes per workgroup: 64 (one wavefront) or 256
   int nontemporal = 1;  // streaming cache hints on loads and stores
-  Shape shape[kNumClasses] = {{1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 14, 2}, {1, 10, 0}, {1, 12, 2}};
+  Shape shape[kNumClasses] = {{1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 14, 2}, {1, 10, 0}, {1, 12, 2},
+                              {1, 16, 0}, {1, 28, 0}};
 };
 Tuning &tuning();
 
