@@ -26,9 +26,10 @@ enum KernelClass {
 
 // vecs: 128-bit vectors each lane keeps in flight per stream {1, 2, 4}.
 // waves: wavefronts resident per CU, 0 = as many as the hardware takes (32).  HBM efficiency falls once
-// much more than ~48 KiB of loads per CU are in flight (the open DRAM pages thrash), so the kernels
-// with several streams per wavefront run faster with fewer resident wavefronts.  The limit is imposed by
-// giving every workgroup a share of the CU's 160 KiB of LDS that it never touches.
+// much more than ~48 KiB of loads per CU are outstanding (measured: the read latency at the memory
+// interface and the L2's read-credit stalls rise, the launch takes 7-13 % more GPU cycles), so the kernels
+// that keep several KiB per wavefront outstanding run faster with fewer resident wavefronts.  The limit is
+// imposed by giving every workgroup a share of the CU's 160 KiB of LDS that it never touches.
 // depth (reduce kernels only): contributors whose loads a wavefront has in flight at a time {1, 2}.
 struct Shape {
   int vecs, waves, depth;
@@ -37,8 +38,19 @@ struct Shape {
 struct Tuning {
   int threads = 64;     // lanes per workgroup: 64 (one wavefront) or 256
   int nontemporal = 1;  // streaming cache hints on loads and stores
-  Shape shape[kNumClasses] = {{1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 0, 0}, {1, 14, 2}, {1, 10, 0}, {1, 12, 2},
-                              {1, 16, 0}, {1, 28, 0}};
+  // Defaults from sweeps on the four large benchmark workloads (one vector per lane everywhere).
+  Shape shape[kNumClasses] = {
+      {1, 0, 0},   // kAccFirstF32
+      {1, 0, 0},   // kAccRmwF32
+      {1, 0, 0},   // kAccFirstBf16
+      {1, 0, 0},   // kAccRmwBf16
+      {1, 0, 0},   // kCopy
+      {1, 14, 2},  // kReduce: contributors in pairs, 14 wavefronts per CU
+      {1, 10, 0},  // kAdamw: four loads per wavefront outstanding, 10 wavefronts per CU
+      {1, 12, 2},  // kReduceAdamw
+      {1, 16, 0},  // kAccSnapF32
+      {1, 28, 0},  // kAccSnapBf16
+  };
 };
 Tuning &tuning();
 
