@@ -95,7 +95,7 @@ enum { RECOVER_FUSED_WRITE_GRAD = 1u }; /* recover_reduce_adamw_step flags */
 typedef struct {
   int32_t W_init;                /* replicas, 1..RECOVER_MAX_REPLICAS */
   int32_t G_init;                /* microbatches per replica per iteration, >= 1 */
-  int64_t n_elems;               /* elements of the shard = tensor_offsets[n_tensors] */
+  int64_t n_elems;               /* elements of the shard = tensor_offsets[n_tensors], 0..RECOVER_MAX_ELEMS */
   int32_t n_tensors;             /* >= 1 */
   const int64_t *tensor_offsets; /* host, n_tensors + 1 non-decreasing element offsets from 0; copied */
   float *const *acc;             /* host array of W_init device pointers, n_elems floats each */
@@ -115,6 +115,9 @@ typedef struct {
 } recover_config;
 
 #define RECOVER_MAX_REPLICAS 64
+/* Largest shard: every kernel launch is one workgroup per 256 elements and a grid holds fewer than 2^31
+ * workgroups in x.  All element and byte offsets are 64-bit throughout. */
+#define RECOVER_MAX_ELEMS (1ll << 38)
 
 /* The failure record of Alg. 2 "Record" plus the PolicyDecision of Alg. 6 (failure case), or the
  * layout of Alg. 7 (commit case), or the current state (recover_query).  The four arrays are

@@ -203,6 +203,8 @@ int recover_init(const recover_config *cfg, recover_ctx **out) {
     return fail(nullptr, RECOVER_ERR_ARG, "recover_init: B = W_init * G_init too large");
   if (cfg->n_tensors < 1 || !cfg->tensor_offsets || cfg->n_elems < 0)
     return fail(nullptr, RECOVER_ERR_ARG, "recover_init: tensor table missing");
+  if (cfg->n_elems > RECOVER_MAX_ELEMS)
+    return fail(nullptr, RECOVER_ERR_ARG, "recover_init: n_elems above RECOVER_MAX_ELEMS (2^38)");
   if (cfg->flags & ~(RECOVER_FLAG_ADAPTIVE | RECOVER_FLAG_ANY_ORDER | RECOVER_FLAG_HOST_ONLY))
     return fail(nullptr, RECOVER_ERR_ARG, "recover_init: unknown flag");
   if (cfg->tensor_offsets[0] != 0 || cfg->tensor_offsets[cfg->n_tensors] != cfg->n_elems)

@@ -116,8 +116,11 @@ def _four_normals(x0, x1, x2, x3):
 
 
 def values(idx, seed, tag, mb_id, it, scale, kind=KIND_NORMAL):
-    """fp32 stream values at element indices `idx` (any integer array)."""
+    """fp32 stream values at element indices `idx` (any integer array; below 2^34 for the Gaussian stream, which
+    packs four elements per 32-bit counter word, below 2^32 for the Student-t stream)."""
     idx = np.asarray(idx, np.uint64)
+    if idx.size and int(idx.max()) >= (1 << 34 if kind == KIND_NORMAL else 1 << 32):
+        raise ValueError("element index beyond the stream's counter word")
     if kind == KIND_NORMAL:
         x = philox4x32_10(idx >> np.uint64(2), mb_id, it, KIND_NORMAL, seed, tag)
         lane = (idx & np.uint64(3)).astype(np.int64)

@@ -153,10 +153,12 @@ extern "C" {
 
 // Fill out[0..n) (device; fp32 if !bf16 else bf16 bit patterns) with stream elements
 // start .. start+n-1.  kind 0 Gaussian, 1 Student-t(3).  Asynchronous on `stream`.
+// The element index goes into one 32-bit counter word: the Gaussian stream packs four elements per counter
+// (indices below 2^34), the Student-t stream one (below 2^32).
 // Returns 0, -1 on a bad argument, -4 on a HIP error.
 int synth_fill(void *out, int bf16, uint64_t start, uint64_t n, uint32_t seed, uint32_t tag, uint32_t mb_id,
                uint32_t iter, double scale, int kind, void *stream) {
-  if (!out || (kind != 0 && kind != 1) || start + n > (1ull << 32)) return -1;
+  if (!out || (kind != 0 && kind != 1) || start + n > (kind == 0 ? 1ull << 34 : 1ull << 32)) return -1;
   if (n == 0) return 0;
   hipStream_t s = (hipStream_t)stream;
   const size_t work = kind == 0 ? ((start + n + 3) >> 2) - (start >> 2) : n;

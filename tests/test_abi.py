@@ -51,6 +51,10 @@ def test_argument_errors():
     assert B.recover_init(0, 2, [0, 8], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
     assert B.recover_init(65, 2, [0, 8], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
     assert B.recover_init(2, 2, [0, 8, 4], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
+    assert B.recover_init(2, 2, [0, (1 << 38) + 1], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)[0] == B.ERR_ARG
+    assert "RECOVER_MAX_ELEMS" in B.recover_last_error(None)
+    code, big = B.recover_init(2, 2, [0, 5, 1 << 38], None, None, 0, 0, 0, 0, flags=B.FLAG_HOST_ONLY)
+    assert code == B.OK and B.recover_destroy(big) == B.OK
     assert B.recover_init(2, 2, [0, 8], [16, 24 + 4], None, 16, 16, 16, 16)[0] == B.ERR_ALIGN
     s = B.Shard(2, 2, [0, 8, 16], host_only=True)
     assert B.recover_accumulate(s.ctx, 2, 0, 0, B.F32, 0, 2) == B.ERR_ARG

@@ -26,15 +26,36 @@ def hp32():
 
 @pytest.mark.parametrize("cid", [2, 3, 4, 5])
 def test_config_matches_oracle_on_sampled_elements(cid):
-    import torch
     c = CONFIGS[cid]
-    W, G, off = c["W"], c["G"], c["off"]
-    N, T = off[-1], len(off) - 1
-    sched = schedule_of(c)
+    N = c["off"][-1]
     # isolated elements, tensor edges, and (on the two large shards) contiguous windows that span whole
     # workgroup tiles, tensor borders and the elements at byte offsets 2^31 and 2^32
     windows = contiguous_windows(N, 24, 1 << 14, seed=cid) if cid in (3, 5) else contiguous_windows(N, 8, 1 << 12, seed=cid)
-    idx, soff = sample_indices(off, (1 << 14) if cid == 4 else (1 << 15), seed=cid, windows=windows)
+    check_against_the_oracle_on_samples(c, "config %d" % cid, (1 << 14) if cid == 4 else (1 << 15), windows, cid)
+
+
+def test_more_than_2_to_the_32_elements():
+    """The largest shard this suite builds: 2^32 + 2^16 + 3 elements in three tensors (5 elements; one that ends at
+    the odd element 2^31 + 7; one that crosses element 2^32, byte offset 2^34, and ends on a ragged tail), bf16
+    gradients, 2 replicas of 17 GB each with snapshots, a failure in the second iteration.  Element indices need
+    more than 32 bits here, byte offsets more than 34; the windows sit on those borders."""
+    E32, E31 = 1 << 32, 1 << 31
+    off = [0, 5, E31 + 7, E32 + (1 << 16) + 3]
+    N = off[-1]
+    c = dict(name="beyond-32-bit", W=2, G=2, off=off, bf16=True, scale=1e-3, kind=S.KIND_NORMAL, seed=11, iters=2,
+             schedule={1: {1: 1}})
+    L = 1 << 13
+    windows = [(0, L), (E31 + 7 - L // 2, L), (E32 - L // 2, L), (N - L, L), ((E32 >> 2) - L // 2, L), ((E31 >> 1) - L // 2, L)]
+    windows += contiguous_windows(N, 12, L, seed=11)[4:]
+    check_against_the_oracle_on_samples(c, c["name"], 1 << 15, windows, 11)
+
+
+def check_against_the_oracle_on_samples(c, label, n_random, windows, seed):
+    import torch
+    W, G, off = c["W"], c["G"], c["off"]
+    N, T = off[-1], len(off) - 1
+    sched = schedule_of(c)
+    idx, soff = sample_indices(off, n_random, seed=seed, windows=windows)
     idx_dev = torch.from_numpy(idx).cuda()
     p0 = S.values(idx, c["seed"], S.TAG_PARAM, 0, 0, 0.02)
     o32 = Proto(W, G, soff, dtype=np.float32)
@@ -77,8 +98,10 @@ def test_config_matches_oracle_on_sampled_elements(cid):
             assert max_rel(gather(got, idx_dev), want) <= 1e-6
         for got, want in ((s.param, o32.param), (s.exp_avg, o32.m), (s.exp_avg_sq, o32.v)):
             assert max_rel(gather(got, idx_dev), want) <= 1e-6
-        print("config %d iteration %d ok, survivors %d" % (cid, t, len(view_hip(s)["alive"])), flush=True)
+        print("%s iteration %d ok, survivors %d" % (label, t, len(view_hip(s)["alive"])), flush=True)
     s.close()
+    del s, eng, gbuf, g_dev
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("one_pass", [False, True])
