@@ -138,6 +138,13 @@ class Leg:
     def ev(self):
         return self.torch.cuda.Event(enable_timing=True)
 
+    def one_pass_tail_bytes(self):
+        """Bytes per element of recover_reduce_adamw_step: one kernel (4 R_c + 24) up to the library's contributor limit,
+        the reduction followed by the update (4 R_c + 32) beyond it."""
+        code, limit = self.B.recover_get_tuning(self.B.TUNE_ONE_PASS_MAX)
+        assert code == 0
+        return 4 * self.W + (24 if self.W <= limit else 32)
+
     def iteration(self, marks=None, snapshot=False, fused=False, snapshot_every=False):
         """One failure-free iteration.  marks: list receiving the event list of the phases.  fused: the one-pass
         reduce+AdamW call; snapshot_every: the one-pass accumulate+snapshot call for every microbatch."""
@@ -255,9 +262,9 @@ class Leg:
         # one-pass variants: reduce+AdamW without writing the gradient (4 R_c + 24 B/element), and
         # accumulate+snapshot at every microbatch (s_g + 12 resp. s_g + 8 instead of s_g + 8 + 8 resp. s_g + 4 + 8)
         dtf = self.timed(ns, fused=True)
-        b_fused = bpe["accumulate"] + 4 * W + 24
+        b_fused = bpe["accumulate"] + self.one_pass_tail_bytes()
         out["fused_reduce_adamw"] = dict(ms_per_step=dtf * 1e3, bytes_per_elem=b_fused, GBps=b_fused * N / dtf / 1e9,
-                                         microbatches_per_s=M / dtf)
+                                         microbatches_per_s=M / dtf, kernels=1 if self.one_pass_tail_bytes() == 4 * W + 24 else 2)
         marks = []
         for _ in range(ns):
             e0, e1 = self.ev(), self.ev()
@@ -273,9 +280,9 @@ class Leg:
         torch.cuda.synchronize()
         fk = sorted(a.elapsed_time(b) for a, b in marks)[len(marks) // 2]
         out["fused_reduce_adamw"]["kernel_ms"] = fk
-        out["fused_reduce_adamw"]["kernel_GBps"] = (4 * W + 24) * N / fk / 1e6
+        out["fused_reduce_adamw"]["kernel_GBps"] = self.one_pass_tail_bytes() * N / fk / 1e6
         dte = self.timed(ns, fused=True, snapshot_every=True)
-        b_every = W * (s_g + 8) + (M - W) * (s_g + 12) + 4 * W + 24
+        b_every = W * (s_g + 8) + (M - W) * (s_g + 12) + self.one_pass_tail_bytes()
         out["fused_snapshot_every_microbatch"] = dict(ms_per_step=dte * 1e3, bytes_per_elem=b_every,
                                                       GBps=b_every * N / dte / 1e9, microbatches_per_s=M / dte)
 
@@ -499,7 +506,7 @@ def main():
         r = lk.measure(max(5, min(40, int(1500.0 / est_ms))), 2, a.settle_seconds)
         if not a.no_extras:
             dtf = lk.timed(max(3, r["steps"] // 4), fused=True)
-            b_fused = lk.bpe["accumulate"] + 4 * lk.W + 24
+            b_fused = lk.bpe["accumulate"] + lk.one_pass_tail_bytes()
             r["fused_reduce_adamw"] = dict(ms_per_step=dtf * 1e3, bytes_per_elem=b_fused, GBps=b_fused * lk.N / dtf / 1e9)
         per["configs[%d]" % (k - 1)] = r
         lk.close()

@@ -225,8 +225,10 @@ int recover_adamw_step_static(recover_ctx *ctx, int slot, int restart, float lr,
 
 /* recover_reduce over all tensors (not in place) followed by recover_adamw_step, in ONE pass over the
  * contributors' buffers and the optimiser state: 4 R_c + 24 bytes per element instead of 4 R_c + 32.  grad_out
- * is written only with RECOVER_FUSED_WRITE_GRAD.  Same checks (Eq. 1), same bits in param, exp_avg, exp_avg_sq
- * (and grad_out if written) as the two calls.  Ends the iteration. */
+ * holds the gradient after the call only with RECOVER_FUSED_WRITE_GRAD (without the flag its content is
+ * unspecified).  Where more than RECOVER_TUNE_ONE_PASS_MAX contributors (default 32) hold a tensor the call
+ * launches the reduction and then the update for it instead, which is faster there.  Same checks (Eq. 1), same
+ * bits in param, exp_avg, exp_avg_sq (and grad_out if asked for) as the two calls.  Ends the iteration. */
 int recover_reduce_adamw_step(recover_ctx *ctx, float lr, float beta1, float beta2, float eps, float weight_decay,
                               uint32_t flags, void *hip_stream);
 
@@ -282,6 +284,8 @@ enum { /* kernel classes that have a launch shape of their own */
 };
 enum { /* keys of recover_set_tuning / recover_get_tuning */
   RECOVER_TUNE_NONTEMPORAL = 1, /* {0, 1}: streaming cache hints on loads and stores */
+  RECOVER_TUNE_ONE_PASS_MAX = 2, /* 0..RECOVER_MAX_REPLICAS: most contributors for which recover_reduce_adamw_step
+                                    runs as one kernel; with more it launches the reduction, then the update */
   RECOVER_TUNE_THREADS = 7,     /* {64, 256}: lanes per workgroup */
   RECOVER_TUNE_VECS = 16,       /* + kernel class: 128-bit vectors per lane per stream {1, 2, 4} */
   RECOVER_TUNE_WAVES = 32,      /* + kernel class: wavefronts resident per CU, 0 = hardware limit, else 2..32 */

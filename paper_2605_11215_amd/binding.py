@@ -26,7 +26,7 @@ FUSED_WRITE_GRAD = 1
 (KERNEL_ACCUMULATE_FIRST_F32, KERNEL_ACCUMULATE_RMW_F32, KERNEL_ACCUMULATE_FIRST_BF16, KERNEL_ACCUMULATE_RMW_BF16,
  KERNEL_COPY, KERNEL_REDUCE, KERNEL_ADAMW, KERNEL_REDUCE_ADAMW, KERNEL_ACCUMULATE_SNAPSHOT_F32,
  KERNEL_ACCUMULATE_SNAPSHOT_BF16, KERNEL_CLASSES) = range(11)
-TUNE_NONTEMPORAL, TUNE_THREADS, TUNE_VECS, TUNE_WAVES, TUNE_DEPTH = 1, 7, 16, 32, 48
+TUNE_NONTEMPORAL, TUNE_ONE_PASS_MAX, TUNE_THREADS, TUNE_VECS, TUNE_WAVES, TUNE_DEPTH = 1, 2, 7, 16, 32, 48
 
 EXPORTS = ["recover_init", "recover_destroy", "recover_accumulate", "recover_accumulate_many",
            "recover_accumulate_snapshot",

@@ -38,6 +38,13 @@ struct Shape {
 struct Tuning {
   int threads = 64;     // lanes per workgroup: 64 (one wavefront) or 256
   int nontemporal = 1;  // streaming cache hints on loads and stores
+  // The one-pass reduce+AdamW kernel is used up to this many contributors; beyond it the same call launches the
+  // reduction and then the update (same bits, 8 more bytes per element).  Measured on 100 M elements: the three
+  // state stores at the end of a long contributor walk cost more than their bytes, and the more the longer the
+  // walk (one pass against two kernels: 1.08 / 1.20 ms at 12 contributors, 2.44 / 2.45 at 32, 3.59 / 3.39 at 48,
+  // 4.62 / 4.38 at 64, whatever the store's cache policy, one or three store streams, state loaded before or
+  // after the walk).
+  int one_pass_max = 32;
   // Defaults from sweeps on the four large benchmark workloads (one vector per lane everywhere).
   Shape shape[kNumClasses] = {
       {1, 0, 0},   // kAccFirstF32
@@ -143,8 +150,11 @@ hipError_t launch_adam_prologue(StepState *st, float lr, float beta1, float beta
                                 hipStream_t s);
 
 // device_args != nullptr: the kernel reads its constants from device memory instead of `h`.
-hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, const AdamArgs &h,
-                        const AdamArgs *device_args, hipStream_t s);
+// Elements [begin, end) of all five buffers.
+hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t begin, size_t end,
+                        const AdamArgs &h, const AdamArgs *device_args, hipStream_t s);
+
+// One pass up to tuning().one_pass_max contributors, else launch_reduce into a.out followed by launch_adamw.
 
 hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v, uint16_t *p_bf16, bool write_grad,
                                size_t begin, size_t end, const AdamArgs &h, const AdamArgs *device_args, hipStream_t s);

@@ -459,13 +459,13 @@ __global__ __launch_bounds__(T) void k_adamw(AdamPtrs s, const f32x4 *__restrict
   });
 }
 
-// Elements [begin, end) one per lane (the tail of a buffer whose length is not a multiple of four).
+// The ragged elements of a range (at most three before its first aligned vector and three after its last), one per lane.
 __global__ __launch_bounds__(64) void k_adamw_ragged(float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
-                                                     const float *__restrict__ g, uint16_t *__restrict__ pb, size_t begin,
-                                                     size_t end, AdamArgs h_arg, const AdamArgs *h_dev) {
+                                                     const float *__restrict__ g, uint16_t *__restrict__ pb, Span sp,
+                                                     AdamArgs h_arg, const AdamArgs *h_dev) {
   const AdamArgs h = h_dev ? *h_dev : h_arg;
-  const size_t i = begin + threadIdx.x;
-  if (i < end) {
+  const size_t i = ragged_index(sp, threadIdx.x);
+  if (threadIdx.x < 8 && i < sp.end) {
     float pp = p[i], mm = m[i], vv = v[i];
     adam1(pp, mm, vv, g[i], h);
     p[i] = pp;
@@ -846,24 +846,24 @@ static AdamPtrs adam_ptrs(float *p, float *m, float *v, uint16_t *p_bf16, size_t
   return q;
 }
 
-hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t n, const AdamArgs &h,
-                        const AdamArgs *device_args, hipStream_t s) {
-  if (n == 0) return hipSuccess;
+hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *p_bf16, size_t begin, size_t end,
+                        const AdamArgs &h, const AdamArgs *device_args, hipStream_t s) {
+  if (begin >= end) return hipSuccess;
+  const Span sp = make_span(begin, end);
   const Shape sh = tuning().shape[kAdamw];
   const int Uv = sh.vecs, Tv = tuning().threads;
-  const size_t nvec = n / 4;
   unsigned grid;
-  if (!grid_for(nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
-  const AdamPtrs q = adam_ptrs(p, m, v, p_bf16, 0);
+  if (!grid_for(sp.nvec, Tv, Uv, &grid)) return hipErrorInvalidConfiguration;
+  const AdamPtrs q = adam_ptrs(p, m, v, p_bf16, sp.vbegin);
   if (grid)
     with_shape(Tv, Uv, tuning().nontemporal, [&](auto t, auto u, auto nt) {
       constexpr int T = decltype(t)::value, U = decltype(u)::value;
       constexpr bool NT = decltype(nt)::value;
       const unsigned lds = lds_share(sh.waves, T);
-      const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
+      const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g + sp.vbegin);
       auto go = [&](auto bf, auto dev) {
         hipLaunchKernelGGL((k_adamw<T, U, NT, decltype(bf)::value, decltype(dev)::value>), dim3(grid), dim3(T), lds, s, q,
-                           g4, nvec, h, device_args);
+                           g4, sp.nvec, h, device_args);
       };
       auto with_dev = [&](auto bf) {
         if (device_args) go(bf, std::true_type{});
@@ -872,8 +872,7 @@ hipError_t launch_adamw(float *p, float *m, float *v, const float *g, uint16_t *
       if (p_bf16) with_dev(std::true_type{});
       else with_dev(std::false_type{});
     });
-  if (nvec * 4 != n)
-    hipLaunchKernelGGL(k_adamw_ragged, dim3(1), dim3(64), 0, s, p, m, v, g, p_bf16, nvec * 4, n, h, device_args);
+  if (ragged(sp)) hipLaunchKernelGGL(k_adamw_ragged, dim3(1), dim3(64), 0, s, p, m, v, g, p_bf16, sp, h, device_args);
   return hipGetLastError();
 }
 
@@ -881,6 +880,10 @@ hipError_t launch_reduce_adamw(const ReduceArgs &a, float *p, float *m, float *v
                                size_t begin, size_t end, const AdamArgs &h, const AdamArgs *device_args,
                                hipStream_t s) {
   if (begin >= end) return hipSuccess;
+  if (a.n_src > tuning().one_pass_max) {
+    if (hipError_t he = launch_reduce(a, begin, end, s)) return he;
+    return launch_adamw(p, m, v, a.out, p_bf16, begin, end, h, device_args, s);
+  }
   const Span sp = make_span(begin, end);
   const Shape sh = tuning().shape[kReduceAdamw];
   const int Uv = sh.vecs, Tv = tuning().threads;

@@ -807,7 +807,7 @@ static int adamw_step_impl(recover_ctx *c, recover::StepState *device_state, boo
   if (int e = prepare_step(c, device_state, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream, &k, "adamw_step"))
     return e;
   if (!c->host_only) {
-    hipError_t he = recover::launch_adamw(c->param, c->exp_avg, c->exp_avg_sq, c->grad_out, c->param_bf16, (size_t)c->N,
+    hipError_t he = recover::launch_adamw(c->param, c->exp_avg, c->exp_avg_sq, c->grad_out, c->param_bf16, 0, (size_t)c->N,
                                           k.args, k.device_args, (hipStream_t)stream);
     if (he != hipSuccess) return fail(c, RECOVER_ERR_HIP, "adamw_step: %s", hipGetErrorString(he));
   }
@@ -939,6 +939,10 @@ int recover_set_tuning(int key, int value) {
       if (value != 0 && value != 1) return RECOVER_ERR_ARG;
       t.nontemporal = value;
       return RECOVER_OK;
+    case RECOVER_TUNE_ONE_PASS_MAX:
+      if (value < 0 || value > RECOVER_MAX_REPLICAS) return RECOVER_ERR_ARG;
+      t.one_pass_max = value;
+      return RECOVER_OK;
   }
   return RECOVER_ERR_ARG;
 }
@@ -961,6 +965,7 @@ int recover_get_tuning(int key, int *value) {
   switch (key) {
     case RECOVER_TUNE_THREADS: *value = t.threads; return RECOVER_OK;
     case RECOVER_TUNE_NONTEMPORAL: *value = t.nontemporal; return RECOVER_OK;
+    case RECOVER_TUNE_ONE_PASS_MAX: *value = t.one_pass_max; return RECOVER_OK;
   }
   return RECOVER_ERR_ARG;
 }

@@ -73,6 +73,10 @@ def test_argument_errors():
     assert B.recover_set_tuning(B.TUNE_WAVES + B.KERNEL_CLASSES, 8) == B.ERR_ARG        # no such kernel class
     assert B.recover_set_tuning(B.TUNE_WAVES + B.KERNEL_COPY, 1) == B.ERR_ARG
     assert B.recover_set_tuning(0, 1) == B.ERR_ARG
+    assert B.recover_get_tuning(B.TUNE_ONE_PASS_MAX) == (B.OK, 32)
+    assert B.recover_set_tuning(B.TUNE_ONE_PASS_MAX, 65) == B.ERR_ARG and B.recover_set_tuning(B.TUNE_ONE_PASS_MAX, -1) == B.ERR_ARG
+    assert B.recover_set_tuning(B.TUNE_ONE_PASS_MAX, 0) == B.OK and B.recover_get_tuning(B.TUNE_ONE_PASS_MAX) == (B.OK, 0)
+    assert B.recover_set_tuning(B.TUNE_ONE_PASS_MAX, 32) == B.OK
     assert B.recover_query(s.ctx, 2)[1]["target"] == [2, 2]        # unchanged by the failed calls
 
 

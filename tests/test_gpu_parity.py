@@ -209,21 +209,23 @@ def test_negative_zero_and_stale_buffers():
 
 def test_launch_shapes_do_not_change_the_bits():
     """Vectors per lane, resident wavefronts per CU, lanes per workgroup, cache hints and the contributor walk
-    of every kernel class: the results are the same bits under all of them, through the separate and through
-    the one-pass calls."""
+    of every kernel class, and the contributor count up to which reduce+AdamW is one kernel (0: never, 2: for
+    some tensors of the failure iteration, 64: always): the results are the same bits under all of them, through
+    the separate and through the one-pass calls."""
     torch = torch_()
     N = OFF[-1]
     g = grads_np(11, N, 1e-3, False)
     ref = None
-    keys = [B.TUNE_NONTEMPORAL, B.TUNE_THREADS, B.TUNE_DEPTH + B.KERNEL_REDUCE, B.TUNE_DEPTH + B.KERNEL_REDUCE_ADAMW] + \
+    keys = [B.TUNE_NONTEMPORAL, B.TUNE_THREADS, B.TUNE_ONE_PASS_MAX, B.TUNE_DEPTH + B.KERNEL_REDUCE,
+            B.TUNE_DEPTH + B.KERNEL_REDUCE_ADAMW] + \
            [B.TUNE_VECS + k for k in range(B.KERNEL_CLASSES)] + [B.TUNE_WAVES + k for k in range(B.KERNEL_CLASSES)]
     defaults = {k: B.recover_get_tuning(k) for k in keys}
     assert all(code == 0 for code, _ in defaults.values())
     try:
         for U, waves in ((1, 0), (2, 8), (4, 2), (1, 32), (2, 13)):
-            for nt, depth, T in ((1, 1, 64), (0, 2, 256), (1, 2, 64), (0, 1, 256)):
+            for nt, depth, T, one_pass in ((1, 1, 64, 0), (0, 2, 256, 64), (1, 2, 64, 2), (0, 1, 256, 32)):
                 for key, val in ((B.TUNE_NONTEMPORAL, nt), (B.TUNE_THREADS, T), (B.TUNE_DEPTH + B.KERNEL_REDUCE, depth),
-                                 (B.TUNE_DEPTH + B.KERNEL_REDUCE_ADAMW, depth)):
+                                 (B.TUNE_DEPTH + B.KERNEL_REDUCE_ADAMW, depth), (B.TUNE_ONE_PASS_MAX, one_pass)):
                     assert B.recover_set_tuning(key, val) == 0
                 for k in range(B.KERNEL_CLASSES):
                     assert B.recover_set_tuning(B.TUNE_VECS + k, U) == 0
@@ -236,7 +238,7 @@ def test_launch_shapes_do_not_change_the_bits():
                     if ref is None:
                         ref = cur
                     for x, y in zip(ref, cur):
-                        assert torch.equal(x, y), (U, waves, nt, depth, T, fuse)
+                        assert torch.equal(x, y), (U, waves, nt, depth, T, one_pass, fuse)
     finally:
         for k, (_, v) in defaults.items():
             assert B.recover_set_tuning(k, v) == 0
