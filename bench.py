@@ -102,6 +102,55 @@ def cpu_baseline(c, pool_slices, iters):
                 seconds=dt, host_cpus=os.cpu_count())
 
 
+def one_pass_study(reps):
+    """Where the one-pass reduce+AdamW kernel stops paying: for R contributors of the configs[3] shard (100,663,296 fp32
+    elements, 12 tensors) the event-timed duration of recover_reduce_adamw_step forced to one kernel
+    (RECOVER_TUNE_ONE_PASS_MAX = 64) and forced to k_reduce followed by k_adamw (= 0)."""
+    import torch
+    from paper_2605_11215_amd import binding as B
+    from paper_2605_11215_amd import synth
+    from paper_2605_11215_amd.synth import reference_np as S
+    from paper_2605_11215_amd.workloads import CONFIGS
+    c = CONFIGS[4]
+    off, N, T = c["off"], c["off"][-1], len(c["off"]) - 1
+    code, default = B.recover_get_tuning(B.TUNE_ONE_PASS_MAX)
+    assert code == 0
+    rows = []
+    try:
+        for R in (4, 8, 12, 16, 24, 32, 40, 48, 64):
+            sh = B.Shard(R, 1, off, device="cuda:0", snapshots=False, slab=True, slab_pad=SLAB["pad"],
+                         extra=[(torch.float32, N)] * 2, contiguous=SLAB["contiguous"])
+            synth.fill_device(sh.param, 1, S.TAG_PARAM, 0, 0, 0.02, n=N)
+            g = [synth.fill_device(x, 1, S.TAG_GRAD, j, 0, 1e-3) for j, x in enumerate(sh.extra)]
+            stream = torch.cuda.current_stream().cuda_stream
+            row = dict(contributors=R)
+            for name, limit in (("one_kernel", 64), ("reduce_then_adamw", 0)):
+                assert B.recover_set_tuning(B.TUNE_ONE_PASS_MAX, limit) == 0
+                marks = []
+                for it in range(reps + 2):
+                    for r in range(R):
+                        assert B.recover_accumulate(sh.ctx, r, r, g[r % 2].data_ptr(), B.F32, 0, T, stream) == 0
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    assert B.recover_reduce_adamw_step(sh.ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"],
+                                                       HP["weight_decay"], 0, stream) == 0
+                    e1.record()
+                    if it >= 2:
+                        marks.append((e0, e1))
+                torch.cuda.synchronize()
+                ms = sorted(x.elapsed_time(y) for x, y in marks)[len(marks) // 2]
+                bpe = 4 * R + (24 if limit else 32)
+                row[name] = dict(ms=ms, bytes_per_elem=bpe, GBps=bpe * N / ms / 1e6)
+            rows.append(row)
+            sh.close()
+            del sh, g
+            torch.cuda.empty_cache()
+    finally:
+        assert B.recover_set_tuning(B.TUNE_ONE_PASS_MAX, default) == 0
+    return {"one_pass_study": "configs[3] shard, 100,663,296 fp32 elements, median of %d calls" % reps,
+            "library_limit": default, "rows": rows}
+
+
 class Leg:
     """One workload resident in HBM: context, gradient pool, and the timed iteration."""
 
@@ -434,6 +483,9 @@ def main():
     ap.add_argument("--realloc", type=int, default=0,
                     help="placement study instead of the benchmark: allocate, time and free the workload's buffers "
                          "this many times in ONE process and print every allocation's kernel rates")
+    ap.add_argument("--one-pass-study", action="store_true",
+                    help="instead of the benchmark: recover_reduce_adamw_step as one kernel against the reduction "
+                         "followed by the update, over the number of contributors, on the 64-replica workload's shard")
     ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -453,6 +505,9 @@ def main():
         assert B.recover_set_tuning(int(k), int(v)) == 0, kv
     torch.cuda.set_device(0)
 
+    if a.one_pass_study:
+        print(json.dumps(one_pass_study(max(4, a.steps // 2))))
+        return
     if a.realloc > 0:
         # Same process, same code, same virtual layout (the slab lands at the same address): what changes from one
         # allocation to the next is the physical memory behind it.  A 1 GiB allocation is kept after every second
