@@ -3,7 +3,7 @@
 // store per lane per access (a wavefront moves 1 KiB of consecutive bytes per instruction),
 // one-wavefront workgroups with ONE tile each (a finished wavefront frees its slot at once; measured
 // 4 % faster than four-wavefront groups), U independent vectors in flight per lane before the first
-// use, 64-bit element indices (a shard can exceed 2^32 bytes), no LDS (no element is used twice) and
+// use, 64-bit element indices (a shard can exceed 2^32 elements), no LDS (no element is used twice) and
 // no atomics (the sums have a fixed order).
 //
 // A wavefront moves only a few KiB in its whole life, so its prologue counts: the kernels take
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(64) void k_adamw_ragged(float *__restrict__ p, floa
 // ---------------------------------------------------------------------------------------------
 // fused reduce + AdamW: the contributor sum of k_reduce (same walk, same order), its division, and the
 // update of k_adamw in one pass; the gradient goes to HBM only if WRITE_GRAD.  4 R_c + 24 (+4) bytes
-// per element.
+// per element.  Launched for up to tuning().one_pass_max contributors (see launch_reduce_adamw).
 // ---------------------------------------------------------------------------------------------
 template <int T, int U, bool NT, bool WRITE_GRAD, bool BF16OUT, int D, bool DEV>
 __global__ __launch_bounds__(T) void k_reduce_adamw(ReduceArgs a, AdamPtrs s, size_t first, size_t nvec, AdamArgs h_arg,
@@ -585,8 +585,8 @@ struct CompareFold {
   }
 };
 
-// Two streams read with 128-bit loads, nothing written but six atomics per wavefront: also the library's
-// read-only bandwidth probe.
+// Two streams read with 128-bit loads, nothing written but six atomics per wavefront.  The 64-bit checksum
+// arithmetic per element keeps it well below the memory's read rate: a verification kernel, not a bandwidth probe.
 __global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, const float *__restrict__ ref, size_t n,
                                                  CompareResult *out) {
   CompareFold f;
