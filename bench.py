@@ -365,7 +365,7 @@ class Leg:
                                what="best of 5 with the library's own kernels on this workload's buffers: copy = "
                                     "recover_snapshot of all replicas (k_copy_many, 1 read : 1 write); compare = "
                                     "recover_compare over two buffers (k_compare: two reads, no write; a verification "
-                                    "kernel with 64-bit checksum arithmetic per element, not a tuned read probe)")
+                                    "kernel with mismatch, NaN and checksum folds per element, two launches per call)")
 
         # Non-blocking restoration (Alg. 5): rewind every replica from its snapshot while the main stream
         # generates the next microbatch's gradient (the stand-in for the extended pass's forward/backward),

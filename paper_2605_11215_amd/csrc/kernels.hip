@@ -536,8 +536,8 @@ __global__ __launch_bounds__(64) void k_reduce_adamw_ragged(ReduceArgs a, float 
 // compare (verification support, off the timed path): bitwise mismatch count, max |x - ref|,
 // max |ref|, NaN count and two position-weighted 64-bit checksums of two fp32 buffers, without
 // moving them to the host.  Each lane folds its elements, a wavefront folds its 64 lanes with
-// cross-lane shuffles, one lane per wavefront adds to the result with integer atomics (sums and
-// maxima of integers do not depend on the order, so the result is reproducible).
+// cross-lane shuffles, the wavefronts of a workgroup fold through LDS, and one lane per workgroup adds to the result
+// with integer atomics (sums and maxima of integers do not depend on the order, so the result is reproducible).
 // ---------------------------------------------------------------------------------------------
 __device__ inline uint64_t wave_sum_u64(uint64_t v) {
 #pragma unroll
@@ -569,6 +569,24 @@ struct CompareFold {
     cr += uint64_t(bb) * (2 * uint64_t(i) + 1);
     take_no_checksum(a, b);
   }
+  // Four consecutive elements 4 v .. 4 v + 3: their weights are 8 v + 1, + 3, + 5, + 7, so the weighted sum is
+  // (8 v + 1)(b0 + b1 + b2 + b3) + 2 (b1 + 2 b2 + 3 b3) modulo 2^64: one wide multiply per vector and buffer.
+  __device__ inline void take4(const f32x4 &a, const f32x4 &b, size_t v) {
+    const uint64_t w = 8 * uint64_t(v) + 1;
+    uint64_t sa = 0, ta = 0, sb = 0, tb = 0;
+#pragma unroll
+    for (int l = 0; l < 4; ++l) {
+      const float al = a[l], bl = b[l];  // by value: a bit cast applied to the vector-element lvalue reads element 0
+      const uint64_t ab = __builtin_bit_cast(uint32_t, al), bb = __builtin_bit_cast(uint32_t, bl);
+      sa += ab;
+      ta += uint64_t(l) * ab;
+      sb += bb;
+      tb += uint64_t(l) * bb;
+      take_no_checksum(al, bl);
+    }
+    cx += w * sa + 2 * ta;
+    cr += w * sb + 2 * tb;
+  }
   __device__ inline void take_no_checksum(float a, float b) {
     const uint32_t ab = __builtin_bit_cast(uint32_t, a), bb = __builtin_bit_cast(uint32_t, b);
     mism += ab != bb;
@@ -585,8 +603,7 @@ struct CompareFold {
   }
 };
 
-// Two streams read with 128-bit loads, nothing written but six atomics per wavefront.  The 64-bit checksum
-// arithmetic per element keeps it well below the memory's read rate: a verification kernel, not a bandwidth probe.
+// Two streams read with 128-bit loads, nothing written but six atomics per wavefront.
 __global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, const float *__restrict__ ref, size_t n,
                                                  CompareResult *out) {
   CompareFold f;
@@ -594,8 +611,7 @@ __global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, co
   const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x), *r4 = reinterpret_cast<const f32x4 *>(ref);
   for (size_t v = size_t(blockIdx.x) * 256 + threadIdx.x; v < nvec; v += size_t(gridDim.x) * 256) {
     const f32x4 a = __builtin_nontemporal_load(x4 + v), b = __builtin_nontemporal_load(r4 + v);
-#pragma unroll
-    for (int l = 0; l < 4; ++l) f.take(a[l], b[l], 4 * v + l);
+    f.take4(a, b, v);
   }
   if (blockIdx.x == 0 && threadIdx.x < 4) {
     const size_t i = nvec * 4 + threadIdx.x;
@@ -603,13 +619,34 @@ __global__ __launch_bounds__(256) void k_compare(const float *__restrict__ x, co
   }
   const uint64_t mism = wave_sum_u64(f.mism), nans = wave_sum_u64(f.nans), cx = wave_sum_u64(f.cx), cr = wave_sum_u64(f.cr);
   const uint32_t mdiff = wave_max_u32(f.mdiff), mref = wave_max_u32(f.mref);
+  // The four wavefronts of the workgroup fold through LDS, so the six atomics (all workgroups hit the same six
+  // words, which serialises them) are issued once per workgroup.
+  __shared__ uint64_t part64[4][4];
+  __shared__ uint32_t part32[4][2];
+  const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) {
-    atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_mismatch), (unsigned long long)mism);
-    atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_nan), (unsigned long long)nans);
-    atomicAdd(reinterpret_cast<unsigned long long *>(&out->checksum_x), (unsigned long long)cx);
-    atomicAdd(reinterpret_cast<unsigned long long *>(&out->checksum_ref), (unsigned long long)cr);
-    atomicMax(&out->max_abs_diff_bits, mdiff);
-    atomicMax(&out->max_abs_ref_bits, mref);
+    part64[wave][0] = mism;
+    part64[wave][1] = nans;
+    part64[wave][2] = cx;
+    part64[wave][3] = cr;
+    part32[wave][0] = mdiff;
+    part32[wave][1] = mref;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t t[4] = {0, 0, 0, 0};
+    uint32_t m0 = 0, m1 = 0;
+    for (int w = 0; w < 4; ++w) {
+      for (int k = 0; k < 4; ++k) t[k] += part64[w][k];
+      m0 = part32[w][0] > m0 ? part32[w][0] : m0;
+      m1 = part32[w][1] > m1 ? part32[w][1] : m1;
+    }
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_mismatch), (unsigned long long)t[0]);
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->n_nan), (unsigned long long)t[1]);
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->checksum_x), (unsigned long long)t[2]);
+    atomicAdd(reinterpret_cast<unsigned long long *>(&out->checksum_ref), (unsigned long long)t[3]);
+    atomicMax(&out->max_abs_diff_bits, m0);
+    atomicMax(&out->max_abs_ref_bits, m1);
   }
 }
 
@@ -929,7 +966,7 @@ hipError_t launch_compare(const float *x, const float *ref, size_t n, CompareRes
   if (n > 0) {
     size_t blocks = (n / 4 + 255) / 256;
     if (blocks < 1) blocks = 1;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks > 256 * 4) blocks = 256 * 4;  // four workgroups of four wavefronts per CU
     hipLaunchKernelGGL(k_compare, dim3((unsigned)blocks), dim3(256), 0, s, x, ref, n, out);
   }
   return hipGetLastError();
