@@ -76,7 +76,9 @@ def check_against_the_oracle_on_samples(c, label, n_random, windows, seed):
         before = [gather(x, idx_dev) for x in (s.param, s.exp_avg, s.exp_avg_sq)]
         a = run_iteration(o32, view_oracle, t, g_cpu, W, **kw)
         run_iteration(o64, view_oracle, t, g_cpu, W, **kw)
-        b = run_iteration(eng, view_hip, t, g_dev, W, **kw)
+        # odd iterations go through the one-pass calls (accumulate+snapshot, reduce+AdamW; with more than 32
+        # contributors the latter launches the reduction and then the update)
+        b = run_iteration(eng, view_hip, t, g_dev, W, fuse=(t % 2 == 1), **kw)
         assert a["ids"] == b["ids"], t
         if c["bf16"] and t == 0:                    # bf16 inputs against the unrounded fp32 samples
             o_raw = Proto(W, G, soff, dtype=np.float64)
