@@ -102,6 +102,54 @@ def cpu_baseline(c, pool_slices, iters):
                 seconds=dt, host_cpus=os.cpu_count())
 
 
+def pair_study(ballast_gib):
+    """Which pairs of buffers stream well together.  140 buffers of the configs[3] shard's size (100,663,296 fp32 elements,
+    2 MiB-aligned, 4 MiB apart) in one physically contiguous slab; a one-replica context per accumulator buffer a, and
+    recover_accumulate (read-modify-write: the second and later microbatches of an iteration) with buffer k as the gradient.
+    Rows: a = 0, the middle, the last buffer; columns: k = 0, 4, 8, ...; and the diagonal (a, a + 4)."""
+    import torch
+    from paper_2605_11215_amd import binding as B
+    from paper_2605_11215_amd.workloads import CONFIGS
+    off = CONFIGS[4]["off"]
+    N, T = off[-1], len(off) - 1
+    NB = 140
+    ballast = torch.empty(ballast_gib << 30, dtype=torch.uint8, device="cuda:0") if ballast_gib else None
+    if ballast is not None:
+        ballast[:: 1 << 20].zero_()
+    owner, bufs = B.alloc_slab([(torch.float32, N)] * NB, "cuda:0", SLAB["pad"], contiguous=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    ctxs = {}
+
+    def rate(a, k):
+        if a not in ctxs:   # one replica, a quota that the study never reaches: every accumulate after the first is RMW
+            code, ctx = B.recover_init(1, 1 << 20, off, [bufs[a].data_ptr()], None, bufs[a].data_ptr(), bufs[a].data_ptr(),
+                                       bufs[a].data_ptr(), bufs[a].data_ptr(), 0, 0, 0)
+            assert code == 0
+            ctxs[a] = [ctx, 0]
+        c = ctxs[a]
+        g = bufs[k].data_ptr()
+        for _ in range(2):
+            assert B.recover_accumulate(c[0], 0, c[1], g, B.F32, 0, T, stream) == 0
+            c[1] += 1
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(6):
+            assert B.recover_accumulate(c[0], 0, c[1], g, B.F32, 0, T, stream) == 0
+            c[1] += 1
+        e1.record()
+        torch.cuda.synchronize()
+        return round(12 * N * 6 / e0.elapsed_time(e1) / 1e6)
+
+    ks = list(range(0, NB, 4))
+    out = {"pair_study": "RMW accumulate GB/s, accumulator buffer a, gradient buffer k of %d buffers of %d fp32 elements in one slab" % (NB, N),
+           "ballast_gib": ballast_gib, "contiguous": isinstance(owner, B.DeviceSlab), "k": ks,
+           "rows": {str(a): [rate(a, k) if k != a else None for k in ks] for a in (0, 68, NB - 1)},
+           "diagonal_a_a_plus_4": [rate(a, a + 4) for a in range(0, NB - 4, 4)]}
+    for c in ctxs.values():
+        B.recover_destroy(c[0])
+    return out
+
+
 def one_pass_study(reps):
     """Where the one-pass reduce+AdamW kernel stops paying: for R contributors of the configs[3] shard (100,663,296 fp32
     elements, 12 tensors) the event-timed duration of recover_reduce_adamw_step forced to one kernel
@@ -486,6 +534,12 @@ def main():
     ap.add_argument("--one-pass-study", action="store_true",
                     help="instead of the benchmark: recover_reduce_adamw_step as one kernel against the reduction "
                          "followed by the update, over the number of contributors, on the 64-replica workload's shard")
+    ap.add_argument("--pair-study", action="store_true",
+                    help="instead of the benchmark: rate of the read-modify-write accumulate for pairs (accumulator, "
+                         "gradient) of 403 MB buffers taken from different places of one 53 GB physically contiguous slab")
+    ap.add_argument("--ballast-gib", type=int, default=0,
+                    help="with --pair-study or --realloc: an ordinary allocation of this size is made first and held, "
+                         "which moves the slab")
     ap.add_argument("--tuning", default="", help="launch-shape sweep: comma list of key=value for recover_set_tuning")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -505,6 +559,9 @@ def main():
         assert B.recover_set_tuning(int(k), int(v)) == 0, kv
     torch.cuda.set_device(0)
 
+    if a.pair_study:
+        print(json.dumps(pair_study(a.ballast_gib)))
+        return
     if a.one_pass_study:
         print(json.dumps(one_pass_study(max(4, a.steps // 2))))
         return
@@ -513,6 +570,9 @@ def main():
         # allocation to the next is the physical memory behind it.  A 1 GiB allocation is kept after every second
         # round so that the driver cannot hand the same frames back.
         rows, keep = [], []
+        if a.ballast_gib:
+            keep.append(torch.empty(a.ballast_gib << 30, dtype=torch.uint8, device="cuda:0"))
+            keep[-1][:: 1 << 20].zero_()
         for i in range(a.realloc):
             lk = Leg(a.workload)
             r = lk.measure(a.steps, a.warmup, min(a.settle_seconds, 3.0))
@@ -523,7 +583,8 @@ def main():
             lk.close()
             if i % 2 == 0:
                 keep.append(torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0"))
-        print(json.dumps({"placement_study": WORKLOAD_TEXT[a.workload], "slab": SLAB["on"], "allocations": rows}))
+        print(json.dumps({"placement_study": WORKLOAD_TEXT[a.workload], "slab": SLAB["on"], "ballast_gib": a.ballast_gib,
+                          "allocations": rows}))
         return
     leg = Leg(a.workload)
     head = leg.measure(a.steps, a.warmup, a.settle_seconds)
