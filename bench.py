@@ -102,7 +102,7 @@ def cpu_baseline(c, pool_slices, iters):
                 seconds=dt, host_cpus=os.cpu_count())
 
 
-def pair_study(ballast_gib):
+def pair_study(ballast_gib, NB=140):
     """Which pairs of buffers stream well together.  140 buffers of the configs[3] shard's size (100,663,296 fp32 elements,
     2 MiB-aligned, 4 MiB apart) in one physically contiguous slab; a one-replica context per accumulator buffer a, and
     recover_accumulate (read-modify-write: the second and later microbatches of an iteration) with buffer k as the gradient.
@@ -112,7 +112,6 @@ def pair_study(ballast_gib):
     from paper_2605_11215_amd.workloads import CONFIGS
     off = CONFIGS[4]["off"]
     N, T = off[-1], len(off) - 1
-    NB = 140
     ballast = torch.empty(ballast_gib << 30, dtype=torch.uint8, device="cuda:0") if ballast_gib else None
     if ballast is not None:
         ballast[:: 1 << 20].zero_()
@@ -141,8 +140,12 @@ def pair_study(ballast_gib):
         return round(12 * N * 6 / e0.elapsed_time(e1) / 1e6)
 
     ks = list(range(0, NB, 4))
+    # every second buffer against buffer 0: '.' = as fast as a neighbour (same zone), 'X' = 5 % or more below, '?' = between
+    near = rate(0, 1)
+    zone_map = "".join("." if r > 0.975 * near else ("X" if r < 0.95 * near else "?") for r in (rate(0, k) for k in range(1, NB, 2)))
     out = {"pair_study": "RMW accumulate GB/s, accumulator buffer a, gradient buffer k of %d buffers of %d fp32 elements in one slab" % (NB, N),
-           "ballast_gib": ballast_gib, "contiguous": isinstance(owner, B.DeviceSlab), "k": ks,
+           "ballast_gib": ballast_gib, "contiguous": isinstance(owner, B.DeviceSlab), "slab_address": hex(owner.data_ptr()),
+           "zone_map_vs_buffer_0": zone_map, "k": ks,
            "rows": {str(a): [rate(a, k) if k != a else None for k in ks] for a in (0, 68, NB - 1)},
            "diagonal_a_a_plus_4": [rate(a, a + 4) for a in range(0, NB - 4, 4)]}
     for c in ctxs.values():
@@ -235,6 +238,13 @@ class Leg:
     def ev(self):
         return self.torch.cuda.Event(enable_timing=True)
 
+    def g_of(self, r, k):
+        """The pool buffer that holds microbatch k of replica r: with the pool size dividing the replica count, buffer c
+        serves replicas c W/POOL .. (c+1) W/POOL - 1 (Shard puts it next to their accumulators)."""
+        if self.W % POOL == 0:
+            return self.gptr[r // (self.W // POOL)]
+        return self.gptr[(k * self.W + r) % POOL]
+
     def one_pass_tail_bytes(self):
         """Bytes per element of recover_reduce_adamw_step: one kernel (4 R_c + 24) up to the library's contributor limit,
         the reduction followed by the update (4 R_c + 32) beyond it."""
@@ -251,13 +261,13 @@ class Leg:
         if e:
             e[0].record()
         for r in range(W):                                    # k = 0: overwrite variant
-            rc = acc_call(ctx, r, r, gptr[r % POOL], gcode, 0, T, stream)
+            rc = acc_call(ctx, r, r, self.g_of(r, 0), gcode, 0, T, stream)
             assert rc == 0, rc
         if e:
             e[1].record()
         for k in range(1, G):                                 # read-modify-write variant
             for r in range(W):
-                rc = acc_call(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream)
+                rc = acc_call(ctx, r, r + W * k, self.g_of(r, k), gcode, 0, T, stream)
                 assert rc == 0, rc
         if e:
             e[2].record()
@@ -367,7 +377,7 @@ class Leg:
             e0, e1 = self.ev(), self.ev()
             for r in range(W):
                 for k in range(G):
-                    assert B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream) == 0
+                    assert B.recover_accumulate(ctx, r, r + W * k, self.g_of(r, k), gcode, 0, T, stream) == 0
             e0.record()
             assert B.recover_reduce_adamw_step(ctx, HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
                                                0, stream) == 0
@@ -388,7 +398,7 @@ class Leg:
         # streams two buffers and writes nothing.
         for k in range(G):
             for r in range(W):
-                assert B.recover_accumulate(ctx, r, r + W * k, gptr[(k * W + r) % POOL], gcode, 0, T, stream) == 0
+                assert B.recover_accumulate(ctx, r, r + W * k, self.g_of(r, k), gcode, 0, T, stream) == 0
         snap_t, rest_t, cmp_t = [], [], []
         res = torch.empty(5, dtype=torch.int64, device="cuda:0")
         for i in range(6):
@@ -450,7 +460,7 @@ class Leg:
             lost = {W // 2 - 1: min(2, G), W - 2: min(2, G)} if W >= 8 else {W // 2 - 1: min(2, G)}
             torch.cuda.synchronize()
             t4 = time.perf_counter()
-            res_ = run_iteration(self.sh, view_shard, 0, lambda t, mb: pool[mb % POOL], W, dying=lost,
+            res_ = run_iteration(self.sh, view_shard, 0, lambda t, mb: pool[(mb % W) * POOL // W if W % POOL == 0 else mb % POOL], W, dying=lost,
                                  fidelity_k=T // 2 or 1, hp=HP)
             torch.cuda.synchronize()
             dtf2 = time.perf_counter() - t4
@@ -471,7 +481,7 @@ class Leg:
         def one(ctx, s):
             for k in range(G):
                 rc, _ = B.recover_accumulate_many(ctx, list(range(W)), [r + W * k for r in range(W)],
-                                                  [gptr[(k * W + r) % POOL] for r in range(W)], gcode, s)
+                                                  [self.g_of(r, k) for r in range(W)], gcode, s)
                 assert rc == 0, rc
             assert B.recover_reduce_adamw_step(ctx, *hp, 0, s) == 0
             assert B.recover_policy_adjust(ctx, [], W)[0] == 0
@@ -537,6 +547,8 @@ def main():
     ap.add_argument("--pair-study", action="store_true",
                     help="instead of the benchmark: rate of the read-modify-write accumulate for pairs (accumulator, "
                          "gradient) of 403 MB buffers taken from different places of one 53 GB physically contiguous slab")
+    ap.add_argument("--pair-buffers", type=int, default=140,
+                    help="with --pair-study: number of 403 MB buffers in the slab (290 = the size of the headline slab)")
     ap.add_argument("--ballast-gib", type=int, default=0,
                     help="with --pair-study or --realloc: an ordinary allocation of this size is made first and held, "
                          "which moves the slab")
@@ -560,7 +572,7 @@ def main():
     torch.cuda.set_device(0)
 
     if a.pair_study:
-        print(json.dumps(pair_study(a.ballast_gib)))
+        print(json.dumps(pair_study(a.ballast_gib, a.pair_buffers)))
         return
     if a.one_pass_study:
         print(json.dumps(one_pass_study(max(4, a.steps // 2))))

@@ -281,20 +281,33 @@ class DeviceSlab:
             pass
 
 
-def alloc_slab(specs, device="cuda:0", pad_bytes=4 << 20, align=2 << 20, contiguous=False):
+def alloc_slab(specs, device="cuda:0", pad_bytes=4 << 20, align=2 << 20, contiguous=False, groups=None, window=0):
     """One device allocation carved into zero-filled flat tensors: specs = [(torch dtype, numel), ...].  Every
     tensor starts `align`-aligned inside the slab and is followed by `pad_bytes` of padding.  A single
     allocation gives the buffers of a context fixed relative placement (separate allocations land wherever
     the driver puts them, and HBM efficiency of the multi-stream kernels then differs from run to run).
     contiguous: ask the driver for physically contiguous memory first (recover_device_alloc) and fall back to an
-    ordinary torch allocation if it cannot provide it.  Returns (owner of the memory, tensors); the owner must
-    outlive the tensors."""
+    ordinary torch allocation if it cannot provide it.
+    groups, window: groups = lists of indices into specs, in address order (every index once); a group that fits into
+    `window` bytes is not laid across a multiple of `window` from the start of the slab, it starts at the next multiple
+    instead.  Measured on MI355X: a large physically contiguous allocation falls into zones at multiples of 32 GiB, and
+    two streams of one kernel launch run 7 % slower together when they come from different zones.
+    Returns (owner of the memory, tensors in the order of specs); the owner must outlive the tensors."""
     import torch
     sizes = [n * torch.empty(0, dtype=dt).element_size() for dt, n in specs]
-    offs, total = [], 0
-    for b in sizes:
-        offs.append(total)
-        total += (b + align - 1) // align * align + pad_bytes
+    room = [(b + align - 1) // align * align + pad_bytes for b in sizes]
+    if groups is None:
+        groups = [list(range(len(specs)))]
+        window = 0
+    assert sorted(i for g in groups for i in g) == list(range(len(specs)))
+    offs, total = [0] * len(specs), 0
+    for g in groups:
+        need = sum(room[i] for i in g)
+        if window and need <= window and total % window + need > window:
+            total = (total // window + 1) * window
+        for i in g:
+            offs[i] = total
+            total += room[i]
     owner, flat = None, None
     if contiguous and str(device).startswith("cuda"):
         try:
@@ -313,6 +326,29 @@ def alloc_slab(specs, device="cuda:0", pad_bytes=4 << 20, align=2 << 20, contigu
     return owner, out
 
 
+def stream_groups(W, n_extra, snapshots, param_bf16):
+    """Index groups for alloc_slab of the buffers [extra..., acc[0..W), grad_out, param, exp_avg, exp_avg_sq, (param_bf16),
+    (snap[0..W))]: buffers that one kernel launch streams together.  With n_extra dividing W the replicas are cut into n_extra
+    runs and extra buffer c (the microbatch gradients of run c) goes with the accumulators of run c; otherwise all extra
+    buffers and accumulators form one group.  Then the reduced gradient with the optimiser state; then the snapshots, cut
+    like the accumulators."""
+    e0, a0 = 0, n_extra
+    st0 = a0 + W
+    n_state = 4 + (1 if param_bf16 else 0)
+    sn0 = st0 + n_state
+    if n_extra and W % n_extra == 0:
+        per = W // n_extra
+        runs = [list(range(c * per, (c + 1) * per)) for c in range(n_extra)]
+        groups = [[e0 + c] + [a0 + r for r in runs[c]] for c in range(n_extra)]
+    else:
+        runs = [list(range(W))]
+        groups = [list(range(e0, e0 + n_extra)) + [a0 + r for r in range(W)]]
+    groups.append(list(range(st0, st0 + n_state)))
+    if snapshots:
+        groups += [[sn0 + r for r in run] for run in runs]
+    return groups
+
+
 class Shard:
     """Buffers of one context allocated with PyTorch on `device`, plus the calls on it.
 
@@ -321,9 +357,12 @@ class Shard:
     current stream."""
 
     def __init__(self, W_init, G_init, tensor_offsets, device="cuda:0", snapshots=True, flags=0, param_bf16=False,
-                 host_only=False, device_step=False, slab=False, slab_pad=4 << 20, extra=(), contiguous=False):
+                 host_only=False, device_step=False, slab=False, slab_pad=4 << 20, extra=(), contiguous=False,
+                 slab_window=32 << 30):
         """slab: all buffers (and the `extra` = [(dtype, numel), ...] tensors, returned in self.extra) are carved
-        from one allocation, see alloc_slab (contiguous: physically contiguous if the driver can)."""
+        from one allocation, see alloc_slab (contiguous: physically contiguous if the driver can; slab_window: groups of
+        buffers that stream together stay inside one window of this many bytes, see stream_groups; 0 = plain sequence).
+        With len(extra) dividing W_init, extra[c] is meant as the gradient buffer of replicas c W/len .. (c+1) W/len - 1."""
         import torch
         self.torch = torch
         self.W, self.G = W_init, G_init
@@ -338,13 +377,13 @@ class Shard:
         else:
             n = max(self.N, 4)
             if slab:
-                # Address order inside the slab: the caller's extra buffers (the microbatch gradients), the accumulators,
-                # the reduced gradient and the optimiser state, the bf16 copy, the snapshots.  Buffers that one launch
-                # streams together are then neighbours; measured: a pair of streams from distant parts of a large
-                # allocation can lie in different zones of physical memory and then runs 7 % slower.
+                # Address order inside the slab: the caller's extra buffers (the microbatch gradients) with the accumulators
+                # they are added to, the reduced gradient and the optimiser state, the snapshots.  Buffers that one launch
+                # streams together are neighbours and, where they fit, inside one 32 GiB window of the slab.
                 specs = list(extra) + [(torch.float32, n)] * (W_init + 4) + ([(torch.bfloat16, n)] if param_bf16 else []) + \
                     ([(torch.float32, n)] * W_init if snapshots else [])
-                self._slab, bufs = alloc_slab(specs, device, slab_pad, contiguous=contiguous)
+                groups = stream_groups(W_init, len(extra), snapshots, param_bf16)
+                self._slab, bufs = alloc_slab(specs, device, slab_pad, contiguous=contiguous, groups=groups, window=slab_window)
                 self.contiguous = isinstance(self._slab, DeviceSlab)
                 z = lambda dt=torch.float32: bufs.pop(0)
                 self.extra = [z() for _ in extra]

@@ -407,3 +407,20 @@ def test_slab_layout_on_the_cpu():
     assert all(float(b.float().abs().sum()) == 0 for b in bufs)
     bufs[0].fill_(1.0)
     assert float(bufs[1].float().abs().sum()) == 0
+    # groups and windows: a group that fits into a window does not straddle a multiple of the window
+    specs = [(torch.float32, 3000)] * 9                                  # 12,000 bytes each -> 12 KiB + 4 KiB of room
+    groups = [[0, 1, 2], [3, 4], [5], [6, 7, 8]]
+    owner, bufs = B.alloc_slab(specs, device="cpu", pad_bytes=4096, align=4096, groups=groups, window=65536)
+    base = bufs[0].data_ptr()
+    rel = [b.data_ptr() - base for b in bufs]
+    assert rel[:3] == [0, 16384, 32768]                                  # 48 KiB, fits before 64 KiB
+    assert rel[3:5] == [65536, 81920]                                    # 32 KiB would cross 64 KiB: next window
+    assert rel[5] == 98304                                               # 16 KiB fits up to 112 KiB
+    assert rel[6:] == [131072, 147456, 163840]                           # 48 KiB from 112 KiB would cross 128 KiB
+    assert all(float(b.abs().sum()) == 0 for b in bufs)
+    owner, bufs = B.alloc_slab(specs, device="cpu", pad_bytes=4096, align=4096, groups=[list(range(9))], window=65536)
+    assert [b.data_ptr() - bufs[0].data_ptr() for b in bufs] == [16384 * i for i in range(9)]   # too big for a window: plain sequence
+    # the groups Shard builds: gradients with their replicas' accumulators, state, snapshots cut like the accumulators
+    assert B.stream_groups(4, 2, True, False) == [[0, 2, 3], [1, 4, 5], [6, 7, 8, 9], [10, 11], [12, 13]]
+    assert B.stream_groups(3, 2, False, True) == [[0, 1, 2, 3, 4], [5, 6, 7, 8, 9]]
+    assert B.stream_groups(2, 0, True, False) == [[0, 1], [2, 3, 4, 5], [6, 7]]
