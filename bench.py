@@ -616,8 +616,9 @@ def main():
         dtf = leg.timed(a.fused_steps, fused=True)
         out["fused_reduce_adamw"] = dict(ms_per_step=dtf * 1e3)
     if not a.no_extras:
-        out.update(leg.extras(head["ms_per_step"], a.steps))
+        # before the extras: their failure leg leaves a replica dead
         out["batched_launches"] = leg.batched(a.steps) if a.workload == 1 else None
+        out.update(leg.extras(head["ms_per_step"], a.steps))
     out["roofline"] = head["roofline"]
     cpu_slices = None
     if not a.no_cpu_baseline:
