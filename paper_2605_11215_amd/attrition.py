@@ -41,10 +41,12 @@ def main(argv=None):
     if a.dump_yaml:
         open(a.dump_yaml, "w").write(schedule.to_yaml(entries))
 
-    sh = B.Shard(W, G, off, device="cuda:0")
+    # one allocation; gradient buffer j next to the accumulators of the replicas it feeds (binding.stream_groups)
+    n_pool = 4 if W % 4 == 0 else 1
+    sh = B.Shard(W, G, off, device="cuda:0", slab=True, contiguous=True,
+                 extra=[(torch.bfloat16 if c["bf16"] else torch.float32, N)] * n_pool)
     synth.fill_device(sh.param, c["seed"], S.TAG_PARAM, 0, 0, 0.02, n=N)
-    pool = [synth.fill_device(torch.empty(N, dtype=torch.bfloat16 if c["bf16"] else torch.float32, device="cuda:0"),
-                              c["seed"], S.TAG_GRAD, j, 0, c["scale"], c["kind"]) for j in range(4)]
+    pool = [synth.fill_device(g, c["seed"], S.TAG_GRAD, j, 0, c["scale"], c["kind"]) for j, g in enumerate(sh.extra)]
     hp = dict(HP)
     rows = []
     for t in range(a.iters):
@@ -52,7 +54,7 @@ def main(argv=None):
         dying, fid = schedule.for_step(entries, t, v["alive"], v["target"], T)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        out = run_iteration(sh, view_shard, t, lambda it, mb: pool[mb % 4], W, dying=dying, fidelity_k=fid, hp=hp)
+        out = run_iteration(sh, view_shard, t, lambda it, mb: pool[(mb % W) * n_pool // W], W, dying=dying, fidelity_k=fid, hp=hp)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         committed = sum(len(x) for x in out["ids"].values())
